@@ -1,0 +1,259 @@
+"""Pins for the oracle's ranking, budget rule and removal-order algorithm (CPU only)."""
+import itertools
+import os
+from fractions import Fraction
+from math import ceil
+
+import numpy as np
+import pytest
+
+import heatkv_inputs as hi
+from oracle import heatkv_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "alg1_hand_example.txt")
+
+
+def _parse_items(tokens):
+    return sorted(tuple(int(x) for x in tok.split(",")) for tok in tokens)
+
+
+def _load_golden():
+    rec = dict(G={}, E={}, A={}, R={}, N=None)
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        p = line.split()
+        if p[0] == "N":
+            rec["N"] = [int(x) for x in p[1:]]
+        elif p[0] in "GEA":
+            rec[p[0]][int(p[1])] = _parse_items(p[2:])
+        elif p[0] == "R":
+            k, l, h = int(p[1]), int(p[2]), int(p[3])
+            rec["R"][(k, l, h)] = [int(x) for x in p[5:]]
+    return rec
+
+
+def test_hand_worked_example_of_algorithm_1():
+    g = _load_golden()
+    L, H, K, s, B = 2, 2, 5, 1, 20
+    t = orc.one_based([1, 2, 3, 4, 5])
+    a, b, c_, d = (1, 1), (1, 2), (2, 1), (2, 2)
+    orders = {2: [c_, a, d, b], 3: [a, c_, b, d], 4: [d, b, a, c_]}
+    N = orc.heads_to_prune(L * H, t, s, B)
+    assert N[1:] == g["N"]
+    sch = orc.heatkv_schedule(orders, N, t, s, L, H, B)
+    for name in "GEA":
+        for k, want in g[name].items():
+            assert sorted(sch[name][k].items()) == want, (name, k)
+    for (k, l, h), want in g["R"].items():
+        assert orc.retained_scales(sch["A"][k], k, l, h, s) == want
+
+
+# Eq. 5 evaluated with exact rationals, b as a fraction, exactly as printed.
+@pytest.mark.parametrize("name", ["layer2b", "stack2b", "stack8b", "serving"])
+def test_eq5_against_rational_arithmetic_and_total_cache_identity(name):
+    cfg = hi.CONFIGS[name]
+    t = orc.one_based(hi.tokens_per_scale(cfg["sides"]))
+    c = orc.cumulative(t)
+    K, s, T = len(t) - 1, cfg["sinks"], cfg["L"] * cfg["H"]
+    b = Fraction(1, cfg["factor"])
+    B = hi.budget_tokens(cfg)
+    assert B == b * T * c[K - 1]
+    N = orc.heads_to_prune(T, t, s, B)
+    for k in range(1, K):
+        if k <= s:
+            assert N[k] == 0
+            continue
+        want = max(0, ceil(T * (c[k] - b * c[K - 1]) / Fraction(c[k] - c[s])))
+        assert N[k] == want
+        # N_k is the minimal count with N c_s + (T-N) c_k <= B (Sec. 3.2)
+        assert N[k] * c[s] + (T - N[k]) * c[k] <= B
+        if N[k] > 0:
+            assert (N[k] - 1) * c[s] + (T - N[k] + 1) * c[k] > B
+    assert all(N[k] <= N[k + 1] for k in range(1, K - 1))
+
+
+def test_eq5_values_for_the_named_configs():
+    # Values worked from Eq. 5 by hand arithmetic for k = 10..12 of the 16-head, 4x case:
+    # (16*2521-25700)/2500 = 5.85 -> 6, (16*4121-25700)/4100 = 9.81 -> 10, (16*6425-25700)/6404 = 12.04 -> 13
+    cfg = hi.CONFIGS["layer2b"]
+    t = orc.one_based(hi.tokens_per_scale(cfg["sides"]))
+    assert orc.heads_to_prune(16, t, 3, 25700)[1:] == [0] * 9 + [6, 10, 13]
+    tt = orc.one_based(hi.tokens_per_scale(hi.SIDES_TINY))
+    # Tiny: T=4, s=1, B=42: k=3: ceil((4*21-42)/(21-1)) = ceil(2.1) = 3
+    assert orc.heads_to_prune(4, tt, 1, 42)[1:] == [0, 0, 3]
+
+
+def test_budget_below_sinks_is_rejected():
+    t = orc.one_based([1, 4, 16, 64])
+    with pytest.raises(ValueError):
+        orc.heads_to_prune(4, t, 2, 4 * 5 - 1)
+
+
+def test_scas_and_cas_against_direct_slices_and_order_direction():
+    rng = np.random.default_rng(0)
+    L, H, K, s = 2, 3, 6, 2
+    beta = np.zeros((L + 1, H + 1, K + 1, K + 1))
+    beta[1:, 1:, 1:, 1:] = np.tril(rng.random((L, H, K, K)))
+    for l in range(1, L + 1):
+        for h in range(1, H + 1):
+            for k in range(s + 1, K):
+                assert abs(orc.s_cas(beta[l, h], K, k) - beta[l, h, k + 1:, k].mean()) < 1e-15
+            assert abs(orc.cas(beta[l, h], K, s) - beta[l, h, K, s + 1:K].sum() / (K - s)) < 1e-15
+    orders = orc.head_orders(beta, L, H, K, s)
+    assert sorted(orders) == list(range(s + 1, K))
+    for i, O in orders.items():
+        assert sorted(O) == [(l, h) for l in range(1, L + 1) for h in range(1, H + 1)]
+        sc = [orc.s_cas(beta[l, h], K, i) for (l, h) in O]
+        assert sc == sorted(sc)  # least dependent first
+
+
+def test_equal_scores_keep_head_id_order():
+    L, H, K, s = 2, 2, 4, 1
+    beta = np.zeros((L + 1, H + 1, K + 1, K + 1))
+    orders = orc.head_orders(beta, L, H, K, s)
+    for O in orders.values():
+        assert O == [(1, 1), (1, 2), (2, 1), (2, 2)]
+
+
+def _random_case(seed, L, H, sides, s, factor_num, factor_den):
+    rng = np.random.default_rng(seed)
+    t0 = hi.tokens_per_scale(sides)
+    t = orc.one_based(t0)
+    c = orc.cumulative(t)
+    K = len(t0)
+    beta0 = np.tril(rng.random((L, H, K, K))).astype(np.float32)
+    beta0 /= beta0.sum(-1, keepdims=True)
+    T = L * H
+    B = (T * c[K - 1] * factor_num) // factor_den
+    return t, c, K, T, B, orc.beta_one_based(beta0)
+
+
+@pytest.mark.parametrize("seed,L,H,sides,s,num,den", [
+    (0, 3, 4, (1, 2, 3, 4, 5, 6), 2, 1, 2),
+    (1, 4, 2, (1, 2, 4, 6, 8, 12, 16), 3, 1, 4),
+    (2, 2, 8, hi.SIDES_1024, 3, 1, 10),
+    (3, 5, 3, (1, 2, 4, 6, 8, 12), 1, 1, 3),
+])
+def test_schedule_invariants(seed, L, H, sides, s, num, den):
+    t, c, K, T, B, beta = _random_case(seed, L, H, sides, s, num, den)
+    N = orc.heads_to_prune(T, t, s, B)
+    orders = orc.head_orders(beta, L, H, K, s)
+    sch = orc.heatkv_schedule(orders, N, t, s, L, H, B)
+    G, E, A = sch["G"], sch["E"], sch["A"]
+    empty = orc._Sets(K, L, H)
+    for k in range(1, K):
+        Gk, Gp = G[k], (G[k - 1] if k > 1 else empty)
+        # each prunable source scale i <= k is removed in exactly N_k heads (Sec. 3.2)
+        for i in range(1, K + 1):
+            want = N[k] if s < i <= k else 0
+            assert int(Gk.m[i].sum()) == want
+        assert not np.any(Gp.m & ~Gk.m)                      # G_{k-1} subset of G_k
+        assert not np.any(E[k].m & ~(Gk.m & ~Gp.m))          # E_k subset of G_k \ G_{k-1}
+        assert np.array_equal(A[k].m, Gp.m | E[k].m)         # A_k = G_{k-1} u E_k
+        assert not np.any(A[k].m & ~A[k + 1].m)              # absent sets only grow
+        # budget after every layer, by the accounting of Alg. 2, and the end-of-scale closed form
+        for layer in range(1, L + 1):
+            assert orc.cache_size_after_layer(k, layer, Gk, Gp, E[k], t, c, s, L, H) <= B
+        # end of scale: every prunable source scale i <= k is missing from exactly N_k heads
+        # (for k <= s the printed CachedTokens is the constant c_s)
+        total = orc.cache_size_after_layer(k, L, Gk, Gp, E[k], t, c, s, L, H)
+        kept = T * c[max(k, s)] - sum(t[i] * N[k] for i in range(s + 1, k + 1))
+        assert total == kept
+    assert np.array_equal(A[K].m, G[K - 1].m)
+
+
+def test_greedy_is_minimal_along_its_own_order():
+    # Dropping the last popped element must break feasibility at some layer.
+    t, c, K, T, B, beta = _random_case(5, 4, 4, (1, 2, 4, 6, 8, 12, 16), 2, 1, 3)
+    L, H, s = 4, 4, 2
+    N = orc.heads_to_prune(T, t, s, B)
+    orders = orc.head_orders(beta, L, H, K, s)
+    rank = {(i, l, h): r for i, O in orders.items() for r, (l, h) in enumerate(O)}
+    sch = orc.heatkv_schedule(orders, N, t, s, L, H, B)
+    seen = 0
+    empty = orc._Sets(K, L, H)
+    for k in range(1, K):
+        Gp = sch["G"][k - 1] if k > 1 else empty
+        E, popped = orc.greedy_early_pruning(k, Gp, sch["G"][k], B, rank, t, c, s, L, H)
+        assert sorted(E.items()) == sorted(sch["E"][k].items())
+        keys = [(-it[1], -it[0], rank[it]) for it in popped]
+        assert keys == sorted(keys)
+        if popped:
+            seen += 1
+            smaller = orc._Sets(K, L, H, popped[:-1])
+            sizes = [orc.cache_size_after_layer(k, l, sch["G"][k], Gp, smaller, t, c, s, L, H) for l in range(1, L + 1)]
+            assert max(sizes) > B
+    assert seen > 0
+
+
+def test_full_budget_prunes_nothing_and_naive_policy_is_feasible():
+    t, c, K, T, B, beta = _random_case(7, 2, 3, (1, 2, 4, 6, 8), 1, 1, 1)
+    L, H, s = 2, 3, 1
+    N = orc.heads_to_prune(T, t, s, B)
+    assert all(n == 0 for n in N)
+    orders = orc.head_orders(beta, L, H, K, s)
+    sch = orc.heatkv_schedule(orders, N, t, s, L, H, B)
+    assert all(len(sch[n][k]) == 0 for n in "GE" for k in range(1, K))
+    t, c, K, T, B, beta = _random_case(8, 3, 3, (1, 2, 4, 6, 8, 12), 1, 1, 3)
+    L, H, s = 3, 3, 1
+    N = orc.heads_to_prune(T, t, s, B)
+    orders = orc.head_orders(beta, L, H, K, s)
+    nv = orc.heatkv_schedule(orders, N, t, s, L, H, B, naive=True)
+    gr = orc.heatkv_schedule(orders, N, t, s, L, H, B)
+    empty = orc._Sets(K, L, H)
+    for k in range(1, K):
+        Gp = nv["G"][k - 1] if k > 1 else empty
+        assert np.array_equal(nv["E"][k].m, nv["G"][k].m & ~Gp.m)
+        assert len(gr["E"][k]) <= len(nv["E"][k])
+        for layer in range(1, L + 1):
+            assert orc.cache_size_after_layer(k, layer, nv["G"][k], Gp, nv["E"][k], t, c, s, L, H) <= B
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_binary_greedy_has_minimum_cardinality_by_brute_force(seed):
+    # Prop. 1: among all feasible subsets of G_k \ G_{k-1}, the greedy one is smallest.
+    rng = np.random.default_rng(seed)
+    L, H, s = 3, 2, 1
+    t = orc.one_based([1, 2, 4, 6, 9])
+    c = orc.cumulative(t)
+    K, T = 5, L * H
+    B = int(T * c[K - 1] * 0.45)
+    N = orc.heads_to_prune(T, t, s, B)
+    heads = [(l, h) for l in range(1, L + 1) for h in range(1, H + 1)]
+    order = [heads[j] for j in rng.permutation(T)]
+    sch = orc.binary_heatkv_schedule(order, N, t, s, L, H, B)
+    empty = orc._Sets(K, L, H)
+    checked = 0
+    for k in range(1, K):
+        Gp = sch["G"][k - 1] if k > 1 else empty
+        cand = [it for it in sch["G"][k].items() if it not in Gp]
+        best = None
+        for r in range(len(cand) + 1):
+            for sub in itertools.combinations(cand, r):
+                Es = orc._Sets(K, L, H, sub)
+                if all(orc.cache_size_after_layer(k, l, sch["G"][k], Gp, Es, t, c, s, L, H, binary=True) <= B
+                       for l in range(1, L + 1)):
+                    best = r
+                    break
+            if best is not None:
+                break
+        assert best is not None and len(sch["E"][k]) == best
+        checked += len(cand) > 0
+    assert checked > 0
+
+
+def test_zero_based_present_view_matches_retained_scales():
+    t, c, K, T, B, beta = _random_case(9, 2, 2, (1, 2, 4, 6, 8), 1, 1, 2)
+    L, H, s = 2, 2, 1
+    N = orc.heads_to_prune(T, t, s, B)
+    sch = orc.heatkv_schedule(orc.head_orders(beta, L, H, K, s), N, t, s, L, H, B)
+    pres = orc.to_zero_based_present(sch["A"], K, L, H, s)
+    assert pres.shape == (K, L, H, K)
+    for k in range(K):
+        assert not pres[k, :, :, k:].any()
+        assert pres[k, :, :, :min(s, k)].all()
+    # once dropped a prior scale never returns
+    for k in range(1, K - 1):
+        assert np.all(pres[k + 1, :, :, :k] <= pres[k, :, :, :k])
