@@ -177,12 +177,20 @@ def head_orders(beta, L, H, K, s):
     return orders
 
 
+def cas_sum(beta_lh, K, s):
+    """The un-normalised sum of Eq. 3 (the 1/(K-s) factor does not change the order)."""
+    acc = 0.0
+    for tau in range(s + 1, K):
+        acc += float(beta_lh[K, tau])
+    return acc
+
+
 def cas_order(beta, L, H, K, s):
-    """Single order O of the binary variant, ascending CAS (Eq. 3)."""
+    """Single order O of the binary variant, ascending CAS (Eq. 3); ties keep (l,h) order."""
     scored = []
     for l in range(1, L + 1):
         for h in range(1, H + 1):
-            scored.append((cas(beta[l, h], K, s), l, h))
+            scored.append((cas_sum(beta[l, h], K, s), l, h))
     scored.sort(key=lambda x: x[0])
     return [(l, h) for _, l, h in scored]
 

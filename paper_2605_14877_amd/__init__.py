@@ -1,0 +1,23 @@
+"""MI355X-native HeatKV hot path: thin ctypes binding over libheatkv.so.
+
+Every step of the path (calibration masses, schedule construction, cache
+append/compaction, attention over the ragged cache) runs inside the library;
+this package only marshals arguments.  PyTorch tensors are used as device
+memory handles and for the current HIP stream.
+"""
+from .binding import (  # noqa: F401
+    HeatKVError,
+    Plan,
+    Shape,
+    VARIANT_BINARY,
+    VARIANT_BINARY_NAIVE,
+    VARIANT_HEATKV,
+    VARIANT_NAIVE,
+    calibrate,
+    heatkv_append_scale,
+    heatkv_attend_scale,
+    heatkv_build_schedule,
+    heatkv_calibrate,
+    heatkv_load_schedule,
+    library_path,
+)

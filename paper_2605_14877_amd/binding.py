@@ -1,0 +1,234 @@
+"""ctypes binding of the C ABI declared in include/heatkv.h (same names, argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libheatkv.so")
+
+F32, BF16 = 0, 1
+VARIANT_HEATKV, VARIANT_BINARY, VARIANT_NAIVE, VARIANT_BINARY_NAIVE = 0, 1, 2, 3
+SET_G, SET_E, SET_A = 0, 1, 2
+_DTYPES = {"f32": F32, "bf16": BF16}
+
+
+class HeatKVError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"heatkv error {code}: {msg}")
+        self.code = code
+
+
+class _CShape(C.Structure):
+    _fields_ = [("L", C.c_int32), ("H", C.c_int32), ("d", C.c_int32), ("K", C.c_int32),
+                ("batch", C.c_int32), ("dtype", C.c_int32), ("t", C.POINTER(C.c_int32))]
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Loads libheatkv.so; there is no fallback when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is not built; run `python -m paper_2605_14877_amd.build`")
+    L = C.CDLL(_LIB_PATH)
+    vp, i32p, u8p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.POINTER(C.c_float)
+    sp = C.POINTER(_CShape)
+    L.heatkv_last_error.restype = C.c_char_p
+    L.heatkv_last_error.argtypes = []
+    L.heatkv_calibrate_workspace_bytes.restype = C.c_size_t
+    L.heatkv_calibrate_workspace_bytes.argtypes = [sp, C.c_int]
+    L.heatkv_calibrate.restype = C.c_int
+    L.heatkv_calibrate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.heatkv_build_schedule.restype = C.c_int
+    L.heatkv_build_schedule.argtypes = [sp, f32p, C.c_uint64, C.c_int, C.c_int, C.POINTER(vp)]
+    L.heatkv_load_schedule.restype = C.c_int
+    L.heatkv_load_schedule.argtypes = [sp, u8p, C.POINTER(vp)]
+    L.heatkv_plan_destroy.restype = None
+    L.heatkv_plan_destroy.argtypes = [vp]
+    L.heatkv_plan_upload.restype = C.c_int
+    L.heatkv_plan_upload.argtypes = [vp]
+    L.heatkv_plan_budget_tokens.restype = C.c_int64
+    L.heatkv_plan_budget_tokens.argtypes = [vp]
+    L.heatkv_plan_N.restype = C.c_int
+    L.heatkv_plan_N.argtypes = [vp, i32p]
+    L.heatkv_plan_order.restype = C.c_int
+    L.heatkv_plan_order.argtypes = [vp, C.c_int, i32p]
+    L.heatkv_plan_sets.restype = C.c_int
+    L.heatkv_plan_sets.argtypes = [vp, C.c_int, C.c_int, u8p]
+    L.heatkv_plan_retained.restype = C.c_int
+    L.heatkv_plan_retained.argtypes = [vp, C.c_int, C.c_int, C.c_int, i32p, i32p]
+    L.heatkv_plan_arena_tokens.restype = C.c_int64
+    L.heatkv_plan_arena_tokens.argtypes = [vp]
+    L.heatkv_plan_arena_bytes.restype = C.c_size_t
+    L.heatkv_plan_arena_bytes.argtypes = [vp]
+    L.heatkv_plan_runs.restype = C.c_int
+    L.heatkv_plan_runs.argtypes = [vp, C.c_int, C.c_int, i32p, i32p]
+    L.heatkv_plan_live_tokens.restype = C.c_int64
+    L.heatkv_plan_live_tokens.argtypes = [vp, C.c_int, C.c_int]
+    L.heatkv_append_scale.restype = C.c_int
+    L.heatkv_append_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp]
+    L.heatkv_attend_workspace_bytes.restype = C.c_size_t
+    L.heatkv_attend_workspace_bytes.argtypes = [vp, C.c_int, C.c_int]
+    L.heatkv_attend_scale.restype = C.c_int
+    L.heatkv_attend_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise HeatKVError(rc, lib().heatkv_last_error().decode())
+
+
+def _i32p(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+class Shape:
+    """Problem shape (Sec. 3.1 notation); keeps the token list alive for the C struct."""
+
+    def __init__(self, L, H, d, t, batch, dtype):
+        self.L, self.H, self.d, self.batch = int(L), int(H), int(d), int(batch)
+        self.t = np.ascontiguousarray(t, dtype=np.int32)
+        self.K = int(self.t.size)
+        self.dtype = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+        self.c_struct = _CShape(self.L, self.H, self.d, self.K, self.batch, self.dtype, _i32p(self.t))
+
+    @property
+    def ref(self):
+        return C.byref(self.c_struct)
+
+    @property
+    def elem_size(self):
+        return 2 if self.dtype == BF16 else 4
+
+
+def _ptr(x):
+    """Device (or host) address of a torch tensor / numpy array / None."""
+    if x is None:
+        return None
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    assert x.is_contiguous()
+    return x.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Plan:
+    """Owner of a heatkv_plan handle."""
+
+    def __init__(self, handle, shape):
+        self.handle = C.c_void_p(handle)
+        self.shape = shape
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.heatkv_plan_destroy(self.handle)
+            self.handle = None
+
+    # --- inspection -----------------------------------------------------
+    @property
+    def budget_tokens(self):
+        return int(lib().heatkv_plan_budget_tokens(self.handle))
+
+    @property
+    def arena_tokens(self):
+        return int(lib().heatkv_plan_arena_tokens(self.handle))
+
+    @property
+    def arena_bytes(self):
+        return int(lib().heatkv_plan_arena_bytes(self.handle))
+
+    def N(self):
+        out = np.zeros(max(self.shape.K - 1, 0), dtype=np.int32)
+        _check(lib().heatkv_plan_N(self.handle, _i32p(out)))
+        return out
+
+    def order(self, i):
+        out = np.zeros(self.shape.L * self.shape.H, dtype=np.int32)
+        _check(lib().heatkv_plan_order(self.handle, i, _i32p(out)))
+        return out
+
+    def sets(self, k, which):
+        out = np.zeros((self.shape.K, self.shape.L * self.shape.H), dtype=np.uint8)
+        _check(lib().heatkv_plan_sets(self.handle, k, which, out.ctypes.data_as(C.POINTER(C.c_uint8))))
+        return out
+
+    def retained(self, k, layer, head):
+        n = C.c_int32(0)
+        _check(lib().heatkv_plan_retained(self.handle, k, layer, head, None, C.byref(n)))
+        out = np.zeros(n.value, dtype=np.int32)
+        if n.value:
+            _check(lib().heatkv_plan_retained(self.handle, k, layer, head, _i32p(out), C.byref(n)))
+        return out
+
+    def runs(self, k, layer):
+        row = np.zeros(self.shape.H, dtype=np.int32)
+        ln = np.zeros(self.shape.H, dtype=np.int32)
+        _check(lib().heatkv_plan_runs(self.handle, k, layer, _i32p(row), _i32p(ln)))
+        return row, ln
+
+    def live_tokens(self, k, layer):
+        return int(lib().heatkv_plan_live_tokens(self.handle, k, layer))
+
+    def upload(self):
+        _check(lib().heatkv_plan_upload(self.handle))
+
+    def attend_workspace_bytes(self, layer, k):
+        return int(lib().heatkv_attend_workspace_bytes(self.handle, layer, k))
+
+
+def heatkv_build_schedule(shape, beta, budget_bytes_per_seq, sinks, variant=VARIANT_HEATKV):
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    assert beta.shape == (shape.L, shape.H, shape.K, shape.K)
+    h = C.c_void_p()
+    _check(lib().heatkv_build_schedule(shape.ref, beta.ctypes.data_as(C.POINTER(C.c_float)),
+                                       int(budget_bytes_per_seq), int(sinks), int(variant), C.byref(h)))
+    return Plan(h.value, shape)
+
+
+def heatkv_load_schedule(shape, present):
+    present = np.ascontiguousarray(present, dtype=np.uint8)
+    assert present.shape == (shape.K, shape.L, shape.H, shape.K)
+    h = C.c_void_p()
+    _check(lib().heatkv_load_schedule(shape.ref, present.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(h)))
+    return Plan(h.value, shape)
+
+
+def calibrate_workspace_bytes(shape, k1):
+    return int(lib().heatkv_calibrate_workspace_bytes(shape.ref, k1))
+
+
+def heatkv_calibrate(shape, layer, k1, q, k_all, sm_scale, mass, ws, stream=None):
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().heatkv_calibrate(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale), _ptr(mass),
+                                  _ptr(ws), ws_bytes, _stream() if stream is None else stream))
+
+
+calibrate = heatkv_calibrate
+
+
+def heatkv_append_scale(plan, layer, k, k_new, v_new, k_arena, v_arena, stream=None):
+    _check(lib().heatkv_append_scale(plan.handle, layer, k, _ptr(k_new), _ptr(v_new), _ptr(k_arena), _ptr(v_arena),
+                                     _stream() if stream is None else stream))
+
+
+def heatkv_attend_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, sm_scale, out, ws=None, stream=None):
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().heatkv_attend_scale(plan.handle, layer, k, _ptr(q), _ptr(k_cur), _ptr(v_cur), _ptr(k_arena),
+                                     _ptr(v_arena), float(sm_scale), _ptr(out), _ptr(ws), ws_bytes,
+                                     _stream() if stream is None else stream))

@@ -1,0 +1,328 @@
+// extern "C" entry points of libheatkv: argument checks, plan life cycle, and
+// the hand-off to the kernel launchers.  No arithmetic of the method lives here.
+#include <cstring>
+#include <new>
+#include <string>
+
+#include <hip/hip_runtime_api.h>
+
+#include "heatkv.h"
+#include "kernels.h"
+#include "plan.h"
+
+namespace heatkv {
+const char* last_error_cstr();
+}
+
+using heatkv::fail;
+
+namespace {
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(HEATKV_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+template <typename T>
+int upload_vec(const std::vector<T>& v, T** dst) {
+  *dst = nullptr;
+  if (v.empty()) return HEATKV_OK;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(dst), v.size() * sizeof(T));
+  if (e != hipSuccess) return fail(HEATKV_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
+  e = hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+  return HEATKV_OK;
+}
+
+void free_device(heatkv::DeviceTables& d) {
+  if (d.run_row) (void)hipFree(d.run_row);
+  if (d.run_len) (void)hipFree(d.run_len);
+  if (d.head_order) (void)hipFree(d.head_order);
+  if (d.descs) (void)hipFree(d.descs);
+  d = heatkv::DeviceTables{};
+}
+
+int ensure_uploaded(heatkv_plan* p) {
+  std::lock_guard<std::mutex> lock(p->upload_mutex);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (p->dev.device == dev) return HEATKV_OK;
+  if (p->dev.device >= 0) return fail(HEATKV_EINVAL, "plan was uploaded to another device");
+  int rc;
+  if ((rc = upload_vec(p->run_row, &p->dev.run_row))) return rc;
+  if ((rc = upload_vec(p->run_len, &p->dev.run_len))) return rc;
+  if ((rc = upload_vec(p->head_order, &p->dev.head_order))) return rc;
+  if ((rc = upload_vec(p->descs, &p->dev.descs))) return rc;
+  p->dev.device = dev;
+  return HEATKV_OK;
+}
+
+int check_plan_index(const heatkv_plan* p, int layer, int k) {
+  if (!p) return fail(HEATKV_EINVAL, "plan is null");
+  if (layer < 0 || layer >= p->L) return fail(HEATKV_EINVAL, "layer out of range");
+  if (k < 0 || k >= p->K) return fail(HEATKV_EINVAL, "scale index out of range");
+  return HEATKV_OK;
+}
+
+int finish_plan(heatkv_plan* p, heatkv_plan** out) {
+  int rc = heatkv::derive_layout(p);
+  if (rc) {
+    delete p;
+    return rc;
+  }
+  *out = p;
+  return HEATKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* heatkv_last_error(void) { return heatkv::last_error_cstr(); }
+
+int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t budget_bytes_per_seq, int sinks,
+                          int variant, heatkv_plan** out) {
+  if (!out) return fail(HEATKV_EINVAL, "out is null");
+  *out = nullptr;
+  if (!beta) return fail(HEATKV_EINVAL, "beta is null");
+  if (variant < 0 || variant > 3) return fail(HEATKV_EINVAL, "unknown variant");
+  heatkv_plan* p = new (std::nothrow) heatkv_plan;
+  if (!p) return fail(HEATKV_ENOMEM, "out of host memory");
+  int rc = heatkv::init_shape(p, shape);
+  if (!rc && (sinks < 0 || sinks > p->K - 2)) rc = fail(HEATKV_EINVAL, "sinks must be in [0, K-2]");
+  if (rc) {
+    delete p;
+    return rc;
+  }
+  p->sinks = sinks;
+  p->variant = variant;
+  p->from_schedule = true;
+  p->B = int64_t(budget_bytes_per_seq / (2u * uint64_t(p->d) * p->elem_size()));
+  try {
+    rc = heatkv::build_sets(p, beta);
+    if (rc) {
+      delete p;
+      return rc;
+    }
+    return finish_plan(p, out);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(HEATKV_ENOMEM, "out of host memory");
+  }
+}
+
+int heatkv_load_schedule(const heatkv_shape* shape, const uint8_t* present, heatkv_plan** out) {
+  if (!out) return fail(HEATKV_EINVAL, "out is null");
+  *out = nullptr;
+  if (!present) return fail(HEATKV_EINVAL, "present is null");
+  heatkv_plan* p = new (std::nothrow) heatkv_plan;
+  if (!p) return fail(HEATKV_ENOMEM, "out of host memory");
+  int rc = heatkv::init_shape(p, shape);
+  if (rc) {
+    delete p;
+    return rc;
+  }
+  try {
+    rc = heatkv::load_pattern(p, present);
+    if (rc) {
+      delete p;
+      return rc;
+    }
+    return finish_plan(p, out);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(HEATKV_ENOMEM, "out of host memory");
+  }
+}
+
+void heatkv_plan_destroy(heatkv_plan* plan) {
+  if (!plan) return;
+  if (plan->dev.device >= 0) free_device(plan->dev);
+  delete plan;
+}
+
+int heatkv_plan_upload(heatkv_plan* plan) {
+  if (!plan) return fail(HEATKV_EINVAL, "plan is null");
+  return ensure_uploaded(plan);
+}
+
+int64_t heatkv_plan_budget_tokens(const heatkv_plan* plan) { return plan ? plan->B : 0; }
+
+int heatkv_plan_N(const heatkv_plan* plan, int32_t* out) {
+  if (!plan || !out) return fail(HEATKV_EINVAL, "null argument");
+  if (!plan->from_schedule) return fail(HEATKV_EINVAL, "plan was loaded from an explicit pattern");
+  std::memcpy(out, plan->N.data(), plan->N.size() * sizeof(int32_t));
+  return HEATKV_OK;
+}
+
+int heatkv_plan_order(const heatkv_plan* plan, int i, int32_t* heads_out) {
+  if (!plan || !heads_out) return fail(HEATKV_EINVAL, "null argument");
+  if (!plan->from_schedule) return fail(HEATKV_EINVAL, "plan was loaded from an explicit pattern");
+  if (i < plan->sinks || i >= plan->K - 1) return fail(HEATKV_EINVAL, "source scale has no order");
+  std::memcpy(heads_out, plan->orders[i].data(), size_t(plan->T) * sizeof(int32_t));
+  return HEATKV_OK;
+}
+
+int heatkv_plan_sets(const heatkv_plan* plan, int k, int which, uint8_t* bitmap) {
+  if (!plan || !bitmap) return fail(HEATKV_EINVAL, "null argument");
+  if (!plan->from_schedule) return fail(HEATKV_EINVAL, "plan was loaded from an explicit pattern");
+  const int kmax = which == HEATKV_SET_A ? plan->K : plan->K - 1;
+  if (k < 0 || k >= kmax) return fail(HEATKV_EINVAL, "scale index out of range");
+  const std::vector<uint8_t>* src = which == HEATKV_SET_G ? &plan->G : which == HEATKV_SET_E ? &plan->E
+                                    : which == HEATKV_SET_A ? &plan->A : nullptr;
+  if (!src) return fail(HEATKV_EINVAL, "unknown set");
+  const size_t KT = size_t(plan->K) * plan->T;
+  std::memcpy(bitmap, src->data() + size_t(k) * KT, KT);
+  return HEATKV_OK;
+}
+
+int heatkv_plan_retained(const heatkv_plan* plan, int k, int layer, int head, int32_t* token_idx, int32_t* n) {
+  int rc = check_plan_index(plan, layer, k);
+  if (rc) return rc;
+  if (!n) return fail(HEATKV_EINVAL, "n is null");
+  if (head < 0 || head >= plan->H) return fail(HEATKV_EINVAL, "head out of range");
+  const uint32_t m = plan->retained[size_t(k) * plan->T + layer * plan->H + head];
+  int32_t cnt = 0;
+  for (int i = 0; i < k; ++i) {
+    if (!(m >> i & 1u)) continue;
+    const int32_t lo = plan->c[i] - plan->t[i];
+    if (token_idx)
+      for (int32_t j = 0; j < plan->t[i]; ++j) token_idx[cnt + j] = lo + j;
+    cnt += plan->t[i];
+  }
+  *n = cnt;
+  return HEATKV_OK;
+}
+
+int64_t heatkv_plan_arena_tokens(const heatkv_plan* plan) { return plan ? plan->arena_tokens : 0; }
+
+size_t heatkv_plan_arena_bytes(const heatkv_plan* plan) {
+  if (!plan) return 0;
+  return size_t(plan->batch) * size_t(plan->arena_tokens) * size_t(plan->d) * plan->elem_size();
+}
+
+int heatkv_plan_runs(const heatkv_plan* plan, int k, int layer, int32_t* row_out, int32_t* len_out) {
+  int rc = check_plan_index(plan, layer, k);
+  if (rc) return rc;
+  if (!row_out || !len_out) return fail(HEATKV_EINVAL, "null argument");
+  std::memcpy(row_out, &plan->run_row[plan->idx(k, layer, 0)], size_t(plan->H) * sizeof(int32_t));
+  std::memcpy(len_out, &plan->run_len[plan->idx(k, layer, 0)], size_t(plan->H) * sizeof(int32_t));
+  return HEATKV_OK;
+}
+
+int64_t heatkv_plan_live_tokens(const heatkv_plan* plan, int k, int layer) {
+  if (check_plan_index(plan, layer, k)) return -1;
+  if (k >= plan->K - 1) return -1;
+  int64_t live = 0;
+  for (int l = 0; l < plan->L; ++l) live += plan->region_size[plan->idx(l <= layer ? k + 1 : k, l)];
+  return live;
+}
+
+int heatkv_append_scale(heatkv_plan* plan, int layer, int k, const void* k_new, const void* v_new, void* k_arena,
+                        void* v_arena, void* stream) {
+  int rc = check_plan_index(plan, layer, k);
+  if (rc) return rc;
+  if (k == plan->K - 1) return HEATKV_OK;
+  if (!k_new || !v_new || !k_arena || !v_arena) return fail(HEATKV_EINVAL, "null tensor pointer");
+  const int ndesc = plan->desc_count[plan->idx(k, layer)];
+  if (ndesc == 0) return HEATKV_OK;
+  if ((rc = ensure_uploaded(plan))) return rc;
+  heatkv::AppendArgs a{};
+  a.row_bytes = int(plan->d * plan->elem_size());
+  a.batch = plan->batch;
+  a.H = plan->H;
+  a.t_k = plan->t[k];
+  a.arena_tokens = plan->arena_tokens;
+  a.descs = plan->dev.descs + plan->desc_begin[plan->idx(k, layer)];
+  a.ndesc = ndesc;
+  a.k_new = k_new;
+  a.v_new = v_new;
+  a.k_arena = k_arena;
+  a.v_arena = v_arena;
+  hipError_t e = heatkv::launch_append(a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "append_scale launch");
+  return HEATKV_OK;
+}
+
+size_t heatkv_attend_workspace_bytes(const heatkv_plan* plan, int layer, int k) {
+  if (check_plan_index(plan, layer, k)) return 0;
+  return heatkv::attend_workspace_bytes(plan->dtype, plan->d, plan->H, plan->batch, plan->t[k],
+                                        plan->max_len[plan->idx(k, layer)]);
+}
+
+int heatkv_attend_scale(heatkv_plan* plan, int layer, int k, const void* q, const void* k_cur, const void* v_cur,
+                        const void* k_arena, const void* v_arena, float sm_scale, void* out, void* ws,
+                        size_t ws_bytes, void* stream) {
+  int rc = check_plan_index(plan, layer, k);
+  if (rc) return rc;
+  if (!q || !k_cur || !v_cur || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
+  const int max_len = plan->max_len[plan->idx(k, layer)];
+  if (max_len > 0 && (!k_arena || !v_arena)) return fail(HEATKV_EINVAL, "null arena pointer");
+  const size_t need = heatkv::attend_workspace_bytes(plan->dtype, plan->d, plan->H, plan->batch, plan->t[k], max_len);
+  if (need > 0 && (!ws || ws_bytes < need)) return fail(HEATKV_EINVAL, "attend workspace too small");
+  if (plan->dtype == HEATKV_BF16 && plan->d != 128)
+    return fail(HEATKV_EINVAL, "bf16 attention supports head dimension 128 only");
+  if ((rc = ensure_uploaded(plan))) return rc;
+  heatkv::AttendArgs a{};
+  a.dtype = plan->dtype;
+  a.d = plan->d;
+  a.H = plan->H;
+  a.batch = plan->batch;
+  a.t_k = plan->t[k];
+  a.arena_tokens = plan->arena_tokens;
+  const size_t off = plan->idx(k, layer, 0);
+  a.run_row = plan->dev.run_row + off;
+  a.run_len = plan->dev.run_len + off;
+  a.head_order = plan->dev.head_order + off;
+  a.max_len = max_len;
+  a.q = q;
+  a.k_cur = k_cur;
+  a.v_cur = v_cur;
+  a.k_arena = k_arena;
+  a.v_arena = v_arena;
+  a.out = out;
+  a.sm_scale = sm_scale;
+  a.ws = ws;
+  a.ws_bytes = ws_bytes;
+  hipError_t e = heatkv::launch_attend(a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "attend_scale launch");
+  return HEATKV_OK;
+}
+
+size_t heatkv_calibrate_workspace_bytes(const heatkv_shape* shape, int k1) {
+  if (heatkv::check_shape(shape)) return 0;
+  if (k1 < 0 || k1 >= shape->K) return 0;
+  return heatkv::calibrate_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K, shape->t[k1]);
+}
+
+int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all, float sm_scale,
+                     float* mass, void* ws, size_t ws_bytes, void* stream) {
+  int rc = heatkv::check_shape(shape);
+  if (rc) return rc;
+  if (layer < 0 || layer >= shape->L) return fail(HEATKV_EINVAL, "layer out of range");
+  if (k1 < 0 || k1 >= shape->K) return fail(HEATKV_EINVAL, "scale index out of range");
+  if (!q || !k_all || !mass) return fail(HEATKV_EINVAL, "null tensor pointer");
+  if (shape->dtype == HEATKV_BF16 && shape->d != 128)
+    return fail(HEATKV_EINVAL, "bf16 calibration supports head dimension 128 only");
+  const size_t need =
+      heatkv::calibrate_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K, shape->t[k1]);
+  if (!ws || ws_bytes < need) return fail(HEATKV_EINVAL, "calibrate workspace too small");
+  heatkv::CalibrateArgs a{};
+  a.dtype = shape->dtype;
+  a.d = shape->d;
+  a.H = shape->H;
+  a.batch = shape->batch;
+  a.K = shape->K;
+  a.k1 = k1;
+  for (int k = 0; k < shape->K; ++k) a.t[k] = shape->t[k];
+  a.q = q;
+  a.k_all = k_all;
+  a.sm_scale = sm_scale;
+  a.mass = mass;
+  a.ws = ws;
+  hipError_t e = heatkv::launch_calibrate(a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "calibrate launch");
+  return HEATKV_OK;
+}
+
+}  // extern "C"

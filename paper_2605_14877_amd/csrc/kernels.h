@@ -1,0 +1,53 @@
+// Launchers of the HIP kernels behind the C ABI.  Each returns a hipError_t as int.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+#include <hip/hip_runtime_api.h>
+
+#include "plan.h"
+
+namespace heatkv {
+
+struct AttendArgs {
+  int dtype, d, H, batch;
+  int t_k;                   // queries (= current-scale keys) per head
+  int64_t arena_tokens;      // rows per batch entry of each arena
+  const int32_t* run_row;    // device [H]
+  const int32_t* run_len;    // device [H]
+  const int32_t* head_order; // device [H]
+  int max_len;               // longest run among the H heads (host copy)
+  const void *q, *k_cur, *v_cur, *k_arena, *v_arena;
+  void* out;
+  float sm_scale;
+  void* ws;
+  size_t ws_bytes;
+};
+
+size_t attend_workspace_bytes(int dtype, int d, int H, int batch, int t_k, int max_len);
+hipError_t launch_attend(const AttendArgs& a, hipStream_t stream);
+
+struct AppendArgs {
+  int row_bytes;             // d * elem_size
+  int batch, H, t_k;
+  int64_t arena_tokens;
+  const CopyDesc* descs;     // device
+  int ndesc;
+  const void *k_new, *v_new;
+  void *k_arena, *v_arena;
+};
+hipError_t launch_append(const AppendArgs& a, hipStream_t stream);
+
+struct CalibrateArgs {
+  int dtype, d, H, batch, K, k1;
+  int32_t t[HEATKV_MAX_SCALES];
+  const void *q, *k_all;
+  float sm_scale;
+  float* mass;
+  void* ws;
+};
+size_t calibrate_workspace_bytes(int dtype, int d, int H, int batch, int K, int t_k1);
+hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);
+
+}  // namespace heatkv

@@ -1,0 +1,209 @@
+"""CPU-side checks of the C ABI: exported symbols, host planner bit-exact against the oracle,
+error paths and the static memory layout.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import heatkv_inputs as hi
+import paper_2605_14877_amd as hk
+from paper_2605_14877_amd import binding
+from oracle import heatkv_oracle as orc
+from tests import harness
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "heatkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(heatkv_[a-z_A-Z0-9]+)\s*\(", text))
+    assert {"heatkv_calibrate", "heatkv_build_schedule", "heatkv_append_scale", "heatkv_attend_scale"} <= names
+    lib = ctypes.CDLL(hk.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def _compare(plan, ref, K, L, H, s):
+    binary = ref["binary"]
+    assert plan.N().tolist() == ref["N"][1:]
+    oz = orc.orders_zero_based(ref["orders"], H)
+    for i in range(s, K - 1):
+        assert plan.order(i).tolist() == oz[i]
+    for k in range(K - 1):
+        assert np.array_equal(plan.sets(k, binding.SET_G), harness.bitmap(ref["sch"]["G"][k + 1], K, L, H, s, binary)), k
+        assert np.array_equal(plan.sets(k, binding.SET_E), harness.bitmap(ref["sch"]["E"][k + 1], K, L, H, s, binary)), k
+    for k in range(K):
+        assert np.array_equal(plan.sets(k, binding.SET_A), harness.bitmap(ref["sch"]["A"][k + 1], K, L, H, s, binary)), k
+    t = ref["t"]
+    for k in range(K):
+        for l in range(L):
+            for h in range(H):
+                kept = [i + 1 for i in range(k) if ref["present"][k, l, h, i]]
+                want = orc.retained_token_indices(t, k + 1, kept)
+                assert np.array_equal(plan.retained(k, l, h), want)
+
+
+@pytest.mark.parametrize("name", ["layer2b", "stack2b", "stack8b", "serving"])
+def test_planner_bit_exact_on_named_configs(name):
+    cfg = hi.CONFIGS[name]
+    L, H, s = cfg["L"], cfg["H"], cfg["sinks"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    K = len(t0)
+    beta0, _ = harness.config_beta(name)
+    B = hi.budget_tokens(cfg)
+    shape = hk.Shape(L, H, cfg["d"], t0, cfg["batch"], cfg["dtype"])
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * cfg["d"] * hi.elem_bytes(cfg["dtype"]), s)
+    assert plan.budget_tokens == B
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
+    if name in ("stack8b", "serving", "stack2b"):
+        # full set comparison; retained lists only on a sample of heads to keep the run short
+        assert plan.N().tolist() == ref["N"][1:]
+        for k in range(K):
+            assert np.array_equal(plan.sets(k, binding.SET_A), harness.bitmap(ref["sch"]["A"][k + 1], K, L, H, s, False))
+        for k in range(K - 1):
+            assert np.array_equal(plan.sets(k, binding.SET_E), harness.bitmap(ref["sch"]["E"][k + 1], K, L, H, s, False))
+            assert np.array_equal(plan.sets(k, binding.SET_G), harness.bitmap(ref["sch"]["G"][k + 1], K, L, H, s, False))
+        rng = np.random.default_rng(0)
+        for _ in range(40):
+            k, l, h = int(rng.integers(K)), int(rng.integers(L)), int(rng.integers(H))
+            kept = [i + 1 for i in range(k) if ref["present"][k, l, h, i]]
+            assert np.array_equal(plan.retained(k, l, h), orc.retained_token_indices(ref["t"], k + 1, kept))
+    else:
+        _compare(plan, ref, K, L, H, s)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("seed,L,H,sides,s,num,den", [
+    (0, 3, 4, (1, 2, 3, 4, 5, 6), 2, 1, 2),
+    (1, 4, 2, (1, 2, 4, 6, 8, 12, 16), 3, 1, 4),
+    (2, 2, 8, hi.SIDES_1024, 3, 1, 10),
+    (3, 5, 3, (1, 2, 4, 6, 8, 12), 1, 1, 3),
+    (4, 1, 4, hi.SIDES_TINY, 1, 1, 2),
+    (5, 6, 1, (1, 2, 4, 6, 8), 0, 2, 5),
+])
+def test_planner_bit_exact_on_random_beta_all_variants(variant, seed, L, H, sides, s, num, den):
+    t0 = hi.tokens_per_scale(sides)
+    K = len(t0)
+    c = hi.cumulative_tokens(t0)
+    B = L * H * c[K - 2] * num // den
+    beta0 = harness.random_beta(seed, L, H, K)
+    # plant exact ties to exercise the tie-break
+    beta0[:, 0] = beta0[:, -1]
+    shape = hk.Shape(L, H, 64, t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * 64 * 4, s, variant)
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, B, variant)
+    _compare(plan, ref, K, L, H, s)
+
+
+def test_layout_is_a_valid_fifo_and_respects_the_budget_accounting():
+    for name in ["layer2b", "stack2b", "stack8b"]:
+        cfg = hi.CONFIGS[name]
+        L, H, s = cfg["L"], cfg["H"], cfg["sinks"]
+        t0 = hi.tokens_per_scale(cfg["sides"])
+        K = len(t0)
+        beta0, _ = harness.config_beta(name)
+        B = hi.budget_tokens(cfg)
+        shape = hk.Shape(L, H, cfg["d"], t0, cfg["batch"], cfg["dtype"])
+        plan = hk.heatkv_build_schedule(shape, beta0, B * 512, s)
+        cap = plan.arena_tokens
+        ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
+        t, c1 = ref["t"], orc.cumulative(ref["t"])
+        runs = {(k, l): plan.runs(k, l) for k in range(K) for l in range(L)}
+        # run lengths = retained tokens; runs of a layer are packed back to back
+        for (k, l), (row, ln) in runs.items():
+            want = [sum(t0[i] for i in range(k) if ref["present"][k, l, h, i]) for h in range(H)]
+            assert ln.tolist() == want
+            assert np.all(row + ln <= cap)
+            assert np.all(row[1:] == row[:-1] + ln[:-1])
+        # generation-order replay: the region written by append(l,k) never overlaps a live region
+        live = {l: (0, 0) for l in range(L)}
+        peak = 0
+        for k in range(K - 1):
+            for l in range(L):
+                row, ln = runs[(k + 1, l)]
+                new = (int(row[0]), int(ln.sum()))
+                for l2, (b0, sz) in live.items():
+                    if sz and new[1]:
+                        assert new[0] + new[1] <= b0 or b0 + sz <= new[0], (k, l, l2)
+                live[l] = new
+                tot = sum(sz for _, sz in live.values())
+                peak = max(peak, tot)
+                assert tot == plan.live_tokens(k, l)
+                # physical rows never exceed what Alg. 2 accounts for at the same checkpoint
+                empty = orc._Sets(K, L, H)
+                if k >= s and k + 1 <= K - 1 and name == "layer2b":
+                    Gp = ref["sch"]["G"][k] if k >= 1 else empty
+                    acc = orc.cache_size_after_layer(k + 1, l + 1, ref["sch"]["G"][k + 1], Gp, ref["sch"]["E"][k + 1],
+                                                     t, c1, s, L, H)
+                    assert tot <= acc <= B
+        assert peak <= B
+        biggest = max(int(runs[(k, l)][1].sum()) for k in range(K) for l in range(L))
+        assert cap <= B + 2 * biggest
+
+
+def test_load_schedule_accepts_seeded_pattern_and_rejects_bad_ones():
+    cfg = hi.CONFIGS["tiny"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    K, L, H = len(t0), cfg["L"], cfg["H"]
+    present = hi.explicit_keep_pattern(7, L, H, t0, 42)
+    kept_tokens = sum(t0[i] for l in range(L) for h in range(H) for i in range(K - 1) if present[K - 1, l, h, i])
+    assert 0 < kept_tokens <= 42
+    shape = hk.Shape(L, H, cfg["d"], t0, 1, "f32")
+    plan = hk.heatkv_load_schedule(shape, present)
+    for k in range(K):
+        for h in range(H):
+            want = orc.retained_token_indices(orc.one_based(t0), k + 1, [i + 1 for i in range(k) if present[k, 0, h, i]])
+            assert np.array_equal(plan.retained(k, 0, h), want)
+    with pytest.raises(hk.HeatKVError) as e:
+        plan.N()
+    assert e.value.code == -1
+    bad = present.copy()
+    bad[1, 0, 0, 2] = 1  # a future scale
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_load_schedule(shape, bad)
+    bad = np.zeros_like(present)
+    bad[3, 0, 0, 0] = 1  # scale 0 absent at k=1,2 and back at k=3
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_load_schedule(shape, bad)
+
+
+def test_error_codes():
+    t0 = hi.tokens_per_scale(hi.SIDES_TINY)
+    shape = hk.Shape(1, 4, 64, t0, 1, "f32")
+    beta = harness.random_beta(0, 1, 4, 4)
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_build_schedule(shape, beta, (4 * 5 - 1) * 512, 2)  # below the sinks (c_s = 5 per head)
+    assert e.value.code == -2
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_build_schedule(shape, beta, 42 * 512, 3)  # sinks > K-2
+    assert e.value.code == -1
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_build_schedule(hk.Shape(1, 4, 48, t0, 1, "f32"), beta, 42 * 512, 1)
+    assert e.value.code == -1
+    plan = hk.heatkv_build_schedule(shape, beta, 42 * 512, 1)
+    assert plan.N().tolist() == [0, 0, 3]
+    with pytest.raises(hk.HeatKVError):
+        plan.order(0)
+    with pytest.raises(hk.HeatKVError):
+        plan.retained(4, 0, 0)
+    # null tensor pointers are rejected before any GPU call
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_attend_scale(plan, 0, 1, None, None, None, None, None, 0.125, None, stream=0)
+    assert e.value.code == -1
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_append_scale(plan, 0, 1, None, None, None, None, stream=0)
+    assert e.value.code == -1
+
+
+def test_full_budget_plan_keeps_everything():
+    t0 = hi.tokens_per_scale(hi.SIDES_TINY)
+    c = hi.cumulative_tokens(t0)
+    shape = hk.Shape(2, 2, 64, t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, harness.random_beta(1, 2, 2, 4), 4 * c[-2] * 512, 1)
+    for k in range(4):
+        for l in range(2):
+            for h in range(2):
+                assert plan.retained(k, l, h).tolist() == list(range(c[k] - t0[k]))
