@@ -1,0 +1,178 @@
+"""GPU parity: the HIP path behind the C ABI against the fp64 oracle on the same seeded bytes.
+
+Tolerances (max-abs): attention 1e-5 for fp32 inputs, 2e-2 for bf16 inputs; calibration masses 1e-4.
+Rankings, schedules and retained-index lists are compared bit-exactly in test_abi_cpu.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import heatkv_inputs as hi
+import paper_2605_14877_amd as hk
+from oracle import heatkv_oracle as orc
+from tests import harness
+from tests.gpu_driver import device_generation, oracle_rows
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _dev(*xs):
+    return tuple(x.cuda() for x in xs)
+
+
+def _check_all(outs, q, k, v, t0, present, layer, sm, tol, sample_from=None, sample_rows=192, seed=0):
+    """Compares every (b,h,k); from scale `sample_from` on only a seeded sample of query rows."""
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    nb, H = q.shape[0], q.shape[1]
+    for kk in range(len(t0)):
+        got = outs[kk].float().cpu().double().numpy()
+        for b in range(nb):
+            for h in range(H):
+                kept = [i for i in range(kk) if present[kk, layer, h, i]]
+                rows = None
+                if sample_from is not None and kk >= sample_from and t0[kk] > sample_rows:
+                    rows = np.sort(rng.choice(t0[kk], size=sample_rows, replace=False))
+                    rows[-1] = t0[kk] - 1
+                want = oracle_rows(q, k, v, t0, kk, b, h, kept, sm, rows)
+                g = got[b, h] if rows is None else got[b, h][rows]
+                err = np.abs(g - want).max()
+                worst = max(worst, err)
+                assert err <= tol, (kk, b, h, err)
+    return worst
+
+
+def test_tiny_fp32_explicit_half_budget_schedule():
+    cfg = hi.CONFIGS["tiny"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    K, L, H = len(t0), cfg["L"], cfg["H"]
+    sm = 1.0 / np.sqrt(cfg["d"])
+    w = hi.head_weights(3, L, H, K)
+    q, k, v = hi.make_qkv(11, 0, cfg, w=w)
+    present = hi.explicit_keep_pattern(7, L, H, t0, hi.budget_tokens(cfg))
+    shape = hk.Shape(L, H, cfg["d"], t0, cfg["batch"], "f32")
+    plan = hk.heatkv_load_schedule(shape, present)
+    outs = device_generation(plan, 0, *_dev(q, k, v), t0, sm)
+    _check_all(outs, q, k, v, t0, present, 0, sm, TOL["f32"])
+    # the order of append and attend within a scale does not change the result
+    outs2 = device_generation(plan, 0, *_dev(q, k, v), t0, sm, append_first=True)
+    for a, b in zip(outs, outs2):
+        assert torch.equal(a, b)
+
+
+def test_tiny_fp32_full_budget_equals_uncompressed_attention():
+    cfg = hi.CONFIGS["tiny"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    c = hi.cumulative_tokens(t0)
+    K, H = len(t0), cfg["H"]
+    sm = 1.0 / np.sqrt(cfg["d"])
+    q, k, v = hi.make_qkv(5, 0, cfg)
+    shape = hk.Shape(1, H, cfg["d"], t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, harness.random_beta(0, 1, H, K), H * c[-2] * 512, 1)
+    outs = device_generation(plan, 0, *_dev(q, k, v), t0, sm)
+    got = torch.cat(outs, dim=2).cpu().double().numpy()
+    # brute force: one block-causal attention over the whole sequence in fp64
+    sc = np.concatenate([np.full(t0[i], i) for i in range(K)])
+    mask = sc[None, :] <= sc[:, None]
+    for h in range(H):
+        s = (q[0, h].double().numpy() @ k[0, h].double().numpy().T) * sm
+        s[~mask] = -np.inf
+        p = np.exp(s - s.max(1, keepdims=True))
+        want = (p / p.sum(1, keepdims=True)) @ v[0, h].double().numpy()
+        assert np.abs(got[0, h] - want).max() <= TOL["f32"]
+
+
+@pytest.mark.parametrize("d,L,H,sides,s,den,batch", [
+    (64, 2, 3, (1, 2, 4, 8, 5), 1, 2, 2),
+    (128, 1, 2, (1, 3, 4, 6, 9), 2, 3, 1),
+])
+def test_fp32_schedule_from_alg1_multi_layer(d, L, H, sides, s, den, batch):
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K = len(t0)
+    sm = 1.0 / np.sqrt(d)
+    cfg = dict(L=L, H=H, d=d, dtype="f32", batch=batch, sides=sides)
+    B = L * H * c[-2] // den
+    beta0 = harness.random_beta(4, L, H, K)
+    shape = hk.Shape(L, H, d, t0, batch, "f32")
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * d * 4, s)
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
+    nbytes = max(plan.arena_bytes, 16)
+    arenas = (torch.zeros(nbytes, dtype=torch.uint8, device="cuda"), torch.zeros(nbytes, dtype=torch.uint8, device="cuda"))
+    qkv = [hi.make_qkv(21, l, cfg) for l in range(L)]
+    dq = [_dev(*x) for x in qkv]
+    # generation order: scale outer, layer inner, one shared arena
+    cN = hi.cumulative_tokens(t0)
+    outs = [[None] * K for _ in range(L)]
+    for kk in range(K):
+        sl = slice(cN[kk] - t0[kk], cN[kk])
+        for l in range(L):
+            qk, kc, vc = (x[:, :, sl].contiguous() for x in dq[l])
+            out = torch.empty_like(qk)
+            hk.heatkv_attend_scale(plan, l, kk, qk, kc, vc, arenas[0], arenas[1], sm, out)
+            hk.heatkv_append_scale(plan, l, kk, kc, vc, arenas[0], arenas[1])
+            outs[l][kk] = out
+    torch.cuda.synchronize()
+    for l in range(L):
+        _check_all(outs[l], *qkv[l], t0, ref["present"], l, sm, TOL["f32"])
+
+
+def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None):
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K = len(t0)
+    d = 128
+    sm = 1.0 / np.sqrt(d)
+    cfg = dict(L=L, H=H, d=d, dtype="bf16", batch=batch, sides=sides)
+    B = L * H * c[-2] // den
+    w = hi.head_weights(seed, L, H, K)
+    beta0 = hi.expected_beta_from_weights(w, t0).astype(np.float32)
+    shape = hk.Shape(L, H, d, t0, batch, "bf16")
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * d * 2, s)
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
+    q, k, v = hi.make_qkv(seed, 0, cfg, w=w)
+    outs = device_generation(plan, 0, *_dev(q, k, v), t0, sm)
+    return _check_all(outs, q, k, v, t0, ref["present"], 0, sm, TOL["bf16"], sample_from=sample_from)
+
+
+def test_bf16_small_ragged_scales():
+    # several key tiles, ragged tails in both the query and the key direction
+    _bf16_case(1, 4, (1, 2, 4, 6, 8, 11, 13), 3, 3, 2, seed=2)
+
+
+def test_bf16_layer2b_full_size():
+    # One Infinity-2B-like layer at its real shape (16 heads, 13 scales, batch 2, 4x budget).
+    cfg = hi.CONFIGS["layer2b"]
+    worst = _bf16_case(1, cfg["H"], cfg["sides"], cfg["sinks"], cfg["factor"], cfg["batch"], seed=9, sample_from=8)
+    print("layer2b worst abs err", worst)
+
+
+def test_calibrate_tiny_fp32_and_bf16_small():
+    for dtype, d, sides, batch, H in (("f32", 64, hi.SIDES_TINY, 1, 4), ("bf16", 128, (1, 2, 4, 6, 8, 12, 16), 2, 3)):
+        t0 = hi.tokens_per_scale(sides)
+        c = hi.cumulative_tokens(t0)
+        K = len(t0)
+        sm = 1.0 / np.sqrt(d)
+        cfg = dict(L=1, H=H, d=d, dtype=dtype, batch=batch, sides=sides)
+        w = hi.head_weights(1, 1, H, K)
+        q, k, v = hi.make_qkv(13, 0, cfg, w=w)
+        dq, dk = _dev(q, k)
+        shape = hk.Shape(1, H, d, t0, batch, dtype)
+        t1 = orc.one_based(t0)
+        for k1 in range(K):
+            qk = dq[:, :, c[k1] - t0[k1]:c[k1]].contiguous()
+            ka = dk[:, :, :c[k1]].contiguous()
+            mass = torch.full((batch, H, K), -1.0, device="cuda")
+            ws = torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device="cuda")
+            hk.heatkv_calibrate(shape, 0, k1, qk, ka, sm, mass, ws)
+            got = mass.cpu().double().numpy()
+            # deterministic: a second run gives the same bits
+            mass2 = torch.empty_like(mass)
+            hk.heatkv_calibrate(shape, 0, k1, qk, ka, sm, mass2, ws)
+            assert torch.equal(mass, mass2)
+            for b in range(batch):
+                for h in range(H):
+                    want = orc.beta_row(q[b, h].double().numpy(), k[b, h].double().numpy(), t1, k1 + 1, sm)[1:]
+                    assert np.abs(got[b, h] - want).max() <= 1e-4, (dtype, k1, b, h)
+            assert np.abs(got.sum(-1) - 1.0).max() <= 1e-4
