@@ -1,0 +1,245 @@
+"""Benchmark of the HeatKV hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic activations:
+calibration masses for every scale (Eq. 2) -> dataset average -> schedule
+construction on the host (Eq. 3-5, Alg. 1) -> for every scale, attention over
+the compressed cache followed by the cache append/compaction.  The default
+workload is one Infinity-2B-like layer (16 heads, d=128, bf16, batch 2,
+13 scales = 10521 tokens, 4x budget).
+
+Prints ONE JSON line.  `value` counts the algorithmic FLOPs of the two
+contraction kernels (calibrate QK^T and attend QK^T + PV over the *retained*
+keys) per second of whole-step wall time; `roofline` is the attention kernel
+alone, timed with HIP events on its own stream inside the timed region;
+`cpu_baseline` is the fp64 NumPy oracle on a bounded sample of the same work.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="layer2b", choices=["layer2b", "serving_layer", "layer8b"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attend-only", action="store_true", help="profiling aid: skip calibrate/schedule in the step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import heatkv_inputs as hi
+    import paper_2605_14877_amd as hk
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    base = {"layer2b": "layer2b", "serving_layer": "serving", "layer8b": "stack8b"}[args.workload]
+    cfg = dict(hi.CONFIGS[base])
+    cfg["L"] = 1  # one layer of the named stack: every attend/append/calibrate call is per layer
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    c = hi.cumulative_tokens(t0)
+    K, H, d, s, nb = len(t0), cfg["H"], cfg["d"], cfg["sinks"], cfg["batch"]
+    esz = hi.elem_bytes(cfg["dtype"])
+    sm = 1.0 / np.sqrt(d)
+    B = hi.budget_tokens(cfg)
+    budget_bytes = B * 2 * d * esz
+
+    w = hi.head_weights(0, 1, H, K)
+    gen_batch = min(nb, 2)
+    q, k, v = hi.make_qkv(0, 0, cfg, w=w, batch=gen_batch)
+    if nb > gen_batch:  # larger batches repeat the generated pair (same shapes and value distribution)
+        rep = nb // gen_batch
+        q, k, v = (x.repeat(rep, 1, 1, 1) for x in (q, k, v))
+    dq, dk, dv = q.to(dev), k.to(dev), v.to(dev)
+    sl = [slice(c[i] - t0[i], c[i]) for i in range(K)]
+    q_s = [dq[:, :, sl[i]].contiguous() for i in range(K)]
+    k_s = [dk[:, :, sl[i]].contiguous() for i in range(K)]
+    v_s = [dv[:, :, sl[i]].contiguous() for i in range(K)]
+    kall_s = [dk[:, :, :c[i]].contiguous() for i in range(K)]
+    out_s = [torch.empty_like(x) for x in q_s]
+    shape = hk.Shape(1, H, d, t0, nb, cfg["dtype"])
+
+    beta = torch.zeros(1, H, K, K, device=dev)
+    mass = torch.empty(nb, H, K, device=dev)
+    cal_ws = [torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, i), 4), dtype=torch.uint8, device=dev)
+              for i in range(K)]
+
+    def calibrate_and_plan():
+        beta.zero_()
+        for k1 in range(K):
+            hk.heatkv_calibrate(shape, 0, k1, q_s[k1], kall_s[k1], sm, mass, cal_ws[k1])
+            hk.heatkv_accumulate_beta(shape, 0, k1, mass, 1.0 / nb, beta)
+        beta_h = beta.cpu().numpy()
+        plan = hk.heatkv_build_schedule(shape, beta_h, budget_bytes, s)
+        plan.upload()
+        return plan
+
+    plan = calibrate_and_plan()
+    arena_bytes = plan.arena_bytes
+    ka = torch.zeros(max(arena_bytes, 16), dtype=torch.uint8, device=dev)
+    va = torch.zeros(max(arena_bytes, 16), dtype=torch.uint8, device=dev)
+    att_ws = [torch.empty(max(plan.attend_workspace_bytes(0, i), 4), dtype=torch.uint8, device=dev) for i in range(K)]
+
+    run_len = [plan.runs(i, 0)[1].astype(np.int64) for i in range(K)]
+    n_keys = [nb * int((run_len[i] + t0[i]).sum()) for i in range(K)]           # sum over (b,h) of n
+    att_flops = [4.0 * t0[i] * d * n_keys[i] for i in range(K)]
+    att_bytes = [2.0 * d * esz * (n_keys[i] + nb * H * t0[i]) for i in range(K)]
+    cal_flops = [2.0 * d * t0[i] * c[i] * nb * H for i in range(K)]
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+          for _ in range(args.steps)]
+    cal_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+
+    def step(i_timed=None):
+        nonlocal plan
+        if not args.attend_only:
+            if i_timed is not None:
+                cal_ev[i_timed][0].record()
+            plan = calibrate_and_plan()
+            if i_timed is not None:
+                cal_ev[i_timed][1].record()
+            assert plan.arena_bytes <= arena_bytes
+        for kk in range(K):
+            if i_timed is not None:
+                ev[i_timed][kk][0].record()
+            hk.heatkv_attend_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk], att_ws[kk])
+            if i_timed is not None:
+                ev[i_timed][kk][1].record()
+            hk.heatkv_append_scale(plan, 0, kk, k_s[kk], v_s[kk], ka, va)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    att_ms = np.array([[ev[i][kk][0].elapsed_time(ev[i][kk][1]) for kk in range(K)] for i in range(args.steps)])
+    att_ms_k = att_ms.mean(0)
+    total_att_ms = float(att_ms_k.sum())
+    step_flops = sum(att_flops) + (0.0 if args.attend_only else sum(cal_flops))
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+    att_tflops = sum(att_flops) / (total_att_ms * 1e-3) / 1e12
+    per_scale = []
+    for kk in range(K):
+        ai = att_flops[kk] / att_bytes[kk]
+        per_scale.append({
+            "k": kk, "t": t0[kk], "ms": round(float(att_ms_k[kk]), 4),
+            "tflops": round(att_flops[kk] / (att_ms_k[kk] * 1e-3) / 1e12, 2),
+            "gbs": round(att_bytes[kk] / (att_ms_k[kk] * 1e-3) / 1e9, 1),
+            "flop_per_byte": round(ai, 1),
+        })
+    # KV-read-bound launches: arithmetic intensity below the chip's ridge (peak flops / peak bytes)
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    small = [kk for kk in range(K) if att_flops[kk] / att_bytes[kk] < ridge]
+    small_gbs = (sum(att_bytes[kk] for kk in small) / (sum(att_ms_k[kk] for kk in small) * 1e-3) / 1e9) if small else None
+    large = [kk for kk in range(K) if kk not in small]
+    large_tflops = (sum(att_flops[kk] for kk in large) / (sum(att_ms_k[kk] for kk in large) * 1e-3) / 1e12) if large else None
+
+    result = {
+        "metric": "attend_scale+calibrate algorithmic TFLOP/s over one hot-path step "
+                  "(calibrate -> schedule -> per-scale attend + append)",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg["dtype"],
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: 1 layer x {H} heads x d{d} {cfg['dtype']}, batch {nb}, "
+                               f"{K} scales ({c[-1]} tokens), {cfg['factor']}x budget, sinks {s}",
+                   "attend_only": bool(args.attend_only)},
+        "attend_scale_tflops": round(att_tflops, 2),
+        "attend_scale_ms_per_step": round(total_att_ms, 4),
+        "attend_pct_of_bf16_peak": round(100 * att_tflops / PEAK_BF16_TFLOPS, 2),
+        "attend_large_scales_tflops": None if large_tflops is None else round(large_tflops, 2),
+        "attend_small_scales_kv_gbs": None if small_gbs is None else round(small_gbs, 1),
+        "attend_small_scales_pct_of_hbm_peak": None if small_gbs is None else round(100 * small_gbs / PEAK_HBM_GBS, 2),
+        "per_image_attention_ms": round(total_att_ms / max(nb // 2, 1), 4),
+        "calibrate_ms_per_step": None if args.attend_only else round(
+            float(np.mean([a.elapsed_time(b) for a, b in cal_ev])), 4),
+        "arena_tokens_over_budget": round(plan.arena_tokens / max(B, 1), 4),
+        "per_scale": per_scale,
+        "roofline": {
+            "kernel": "attend_bf16_d128_kernel",
+            "bound": "mfma",
+            "achieved": round(att_tflops, 2),
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4),
+            "traffic": None,
+            "flops_per_step": sum(att_flops),
+            "launches_per_step": K,
+            "avg_launch_ms": round(total_att_ms / K, 4),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(q, k, v, t0, plan, sm, d)
+    print(json.dumps(result))
+
+
+def cpu_baseline(q, k, v, t0, plan, sm, d):
+    """Times the fp64 oracle's attend_scale on a bounded sample: batch row 0, heads 0-1, every scale."""
+    from oracle import heatkv_oracle as orc
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    t1 = orc.one_based(t0)
+    K = len(t0)
+    heads = [0, 1]
+    flops = 0.0
+    data = {h: tuple(x[0, h].double().numpy() for x in (q, k, v)) for h in heads}
+    kept = {}
+    for kk in range(K):
+        for h in heads:
+            idx = plan.retained(kk, 0, h)
+            # which whole scales the retained positions cover (the plan only supplies the index list)
+            c0 = np.cumsum([0] + list(t0))
+            kept[(kk, h)] = [i + 1 for i in range(kk) if idx.size and np.any(idx == c0[i])]
+            flops += 4.0 * t0[kk] * d * (idx.size + t0[kk])
+    t_a = time.perf_counter()
+    for kk in range(K):
+        for h in heads:
+            qq, kk_, vv = data[h]
+            orc.attend_scale(qq, kk_, vv, t1, kk + 1, kept[(kk, h)], sm)
+    dt = time.perf_counter() - t_a
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"oracle attend_scale, batch row 0, heads 0-1, all {K} scales "
+                      f"({flops / 1e9:.1f} GFLOP algorithmic, {dt:.1f} s)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -93,6 +93,17 @@ size_t heatkv_calibrate_workspace_bytes(const heatkv_shape* shape, int k1);
 int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
                      float sm_scale, float* mass, void* ws, size_t ws_bytes, void* stream);
 
+/* Dataset average of Eq. 2 (Sec. 3.1: beta is the mean of beta^d over the
+ * calibration set; every batch row is one data point):
+ *     beta[layer][h][k1][k2] += weight * sum_b mass[b][h][k2]
+ * with weight = 1 / (number of data points).  Batch rows are added in index
+ * order by one thread per entry, so the result is reproducible.
+ * mass  device fp32 [batch][H][K] as written by heatkv_calibrate
+ * beta  device fp32 [L][H][K][K], zero-initialised by the caller before the first call
+ */
+int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const float* mass, float weight,
+                           float* beta, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Schedule construction (Sec. 3.1 Eq. 3-4, Sec. 3.2 Eq. 5, Sec. 3.3 Alg. 1, App. A Alg. 2).
  * Host only, integer arithmetic except for the fp64 sums that rank the heads.

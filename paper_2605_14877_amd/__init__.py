@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     VARIANT_HEATKV,
     VARIANT_NAIVE,
     calibrate,
+    heatkv_accumulate_beta,
     heatkv_append_scale,
     heatkv_attend_scale,
     heatkv_build_schedule,

@@ -40,6 +40,9 @@ def lib():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is not built; run `python -m paper_2605_14877_amd.build`")
+    # The library must share PyTorch's HIP runtime (streams and device pointers cross the boundary):
+    # importing torch first makes its libamdhip64.so.7 the one the dynamic linker binds us to.
+    import torch  # noqa: F401
     L = C.CDLL(_LIB_PATH)
     vp, i32p, u8p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.POINTER(C.c_float)
     sp = C.POINTER(_CShape)
@@ -49,6 +52,8 @@ def lib():
     L.heatkv_calibrate_workspace_bytes.argtypes = [sp, C.c_int]
     L.heatkv_calibrate.restype = C.c_int
     L.heatkv_calibrate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.heatkv_accumulate_beta.restype = C.c_int
+    L.heatkv_accumulate_beta.argtypes = [sp, C.c_int, C.c_int, vp, C.c_float, vp, vp]
     L.heatkv_build_schedule.restype = C.c_int
     L.heatkv_build_schedule.argtypes = [sp, f32p, C.c_uint64, C.c_int, C.c_int, C.POINTER(vp)]
     L.heatkv_load_schedule.restype = C.c_int
@@ -220,6 +225,11 @@ def heatkv_calibrate(shape, layer, k1, q, k_all, sm_scale, mass, ws, stream=None
 
 
 calibrate = heatkv_calibrate
+
+
+def heatkv_accumulate_beta(shape, layer, k1, mass, weight, beta, stream=None):
+    _check(lib().heatkv_accumulate_beta(shape.ref, layer, k1, _ptr(mass), float(weight), _ptr(beta),
+                                        _stream() if stream is None else stream))
 
 
 def heatkv_append_scale(plan, layer, k, k_new, v_new, k_arena, v_arena, stream=None):

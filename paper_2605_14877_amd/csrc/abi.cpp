@@ -325,4 +325,17 @@ int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q
   return HEATKV_OK;
 }
 
+int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const float* mass, float weight, float* beta,
+                           void* stream) {
+  int rc = heatkv::check_shape(shape);
+  if (rc) return rc;
+  if (layer < 0 || layer >= shape->L) return fail(HEATKV_EINVAL, "layer out of range");
+  if (k1 < 0 || k1 >= shape->K) return fail(HEATKV_EINVAL, "scale index out of range");
+  if (!mass || !beta) return fail(HEATKV_EINVAL, "null tensor pointer");
+  hipError_t e = heatkv::launch_accumulate_beta(shape->H, shape->batch, shape->K, layer, k1, mass, weight, beta,
+                                                static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "accumulate_beta launch");
+  return HEATKV_OK;
+}
+
 }  // extern "C"

@@ -261,6 +261,16 @@ __global__ void calibrate_finish_kernel(CalibParams p) {
   p.mass[i] = v;
 }
 
+__global__ void accumulate_beta_kernel(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
+                                       float* beta) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= H * K) return;
+  const int h = i / K, k2 = i % K;
+  float v = 0.f;
+  for (int b = 0; b < batch; ++b) v += mass[(static_cast<long long>(b) * H + h) * K + k2];
+  beta[((static_cast<long long>(layer) * H + h) * K + k1) * K + k2] += weight * v;
+}
+
 int queries_per_tile(int dtype) { return dtype == HEATKV_BF16 ? CBM : FQ; }
 
 }  // namespace
@@ -306,6 +316,14 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
   if (e != hipSuccess) return e;
   const int total = a.batch * a.H * a.K;
   hipLaunchKernelGGL(calibrate_finish_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
+                                  float* beta, hipStream_t stream) {
+  const int total = H * K;
+  hipLaunchKernelGGL(accumulate_beta_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, H, batch, K, layer, k1,
+                     mass, weight, beta);
   return hipGetLastError();
 }
 

@@ -49,5 +49,8 @@ struct CalibrateArgs {
 };
 size_t calibrate_workspace_bytes(int dtype, int d, int H, int batch, int K, int t_k1);
 hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);
+// beta[(layer*H + h)*K*K + k1*K + k2] += weight * sum_b mass[(b*H + h)*K + k2]
+hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
+                                  float* beta, hipStream_t stream);
 
 }  // namespace heatkv
