@@ -6,6 +6,8 @@
 // the current scale.  Both kernels walk this virtual key sequence in tiles,
 // keep running row maxima and row sums in fp32 (online softmax) and normalise
 // once at the end.
+#include <type_traits>
+
 #include "device_util.h"
 #include "kernels.h"
 
@@ -36,15 +38,21 @@ struct AttendParams {
 // already sit in the B-operand layout of the second product O^T += V^T P^T.
 // V^T is read out of the row-major LDS tile with the transposing LDS read.
 // ---------------------------------------------------------------------------
-constexpr int BM = 128;    // queries per workgroup
 constexpr int BN = 64;     // keys per tile
 constexpr int D128 = 128;
-constexpr int KSTR = 136;  // LDS row stride of the K tile in elements (272 B)
-constexpr int VSTR = 144;  // LDS row stride of the V tile in elements (288 B)
+constexpr int KSTR = 136;  // LDS row stride of the K tile in elements (272 B: conflict-free 16-byte row reads)
+constexpr int VSTR = 160;  // LDS row stride of the V tile in elements (320 B: best for the transposing read)
 
-__global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p) {
+// NB = 32-query blocks per wavefront.  NB = 2 (256 queries per workgroup, one
+// wavefront per SIMD, up to 512 registers) halves the LDS traffic per flop: every
+// K or V operand fetched from LDS feeds two matrix instructions.  NB = 1 (128
+// queries per workgroup, two wavefronts per SIMD) keeps more workgroups in
+// flight for the short scales.
+template <int NB>
+__global__ __launch_bounds__(256, (NB == 1 ? 2 : 1)) void attend_bf16_d128_kernel(AttendParams p) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * KSTR];
   __shared__ __attribute__((aligned(16))) bf16_t Vs[BN * VSTR];
+  constexpr int BM = 128 * NB;  // queries per workgroup
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = lane & 31, hl = lane >> 5;
@@ -65,41 +73,47 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   const bf16_t* k_cur = static_cast<const bf16_t*>(p.k_cur) + cur_off;
   const bf16_t* v_cur = static_cast<const bf16_t*>(p.v_cur) + cur_off;
 
-  // Q as B operand: lane (n, hl) holds Q[row][16*ks + 8*hl .. +7] for ks = 0..7.
-  const int q_row = qt * BM + wave * 32 + n;
-  const int q_row_ld = q_row < t_k ? q_row : t_k - 1;
-  bf16x8 qreg[8];
-  {
-    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + cur_off + static_cast<long long>(q_row_ld) * D128 + 8 * hl;
+  // Q as B operand: lane (n, hl) holds Q[row][16*ks + 8*hl .. +7] for ks = 0..7, for each of its NB rows.
+  int q_row[NB];
+  bf16x8 qreg[NB][8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+  for (int nb = 0; nb < NB; ++nb) {
+    q_row[nb] = qt * BM + wave * (32 * NB) + 32 * nb + n;
+    const int ld = q_row[nb] < t_k ? q_row[nb] : t_k - 1;
+    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + cur_off + static_cast<long long>(ld) * D128 + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
 
-  f32x16 o[4];
+  f32x16 o[NB][4];
+  float m_run[NB], l_run[NB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int nb = 0; nb < NB; ++nb) {
+    m_run[nb] = -INFINITY;
+    l_run[nb] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[nb][i][r] = 0.f;
+  }
   const float c = p.sm_scale * kLog2e;
 
   const int n_tiles = (n_total + BN - 1) / BN;
   uint4 kbuf[4], vbuf[4];
 
+  // Global -> register stage of the next tile.  Rows past the end of the key sequence re-read the last
+  // valid row (finite data); their scores are masked to -inf in the last tile, so they contribute nothing.
   auto load_tile = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int chunk = tid + 256 * i;
       const int row = chunk >> 4, col = chunk & 15;
-      const int g = tile * BN + row;
-      if (g < n_total) {
-        const long long off = (g < n_prior ? static_cast<long long>(g) : static_cast<long long>(g - n_prior)) * D128 + col * 8;
-        kbuf[i] = ldg16((g < n_prior ? k_prior : k_cur) + off);
-        vbuf[i] = ldg16((g < n_prior ? v_prior : v_cur) + off);
-      } else {
-        kbuf[i] = make_uint4(0, 0, 0, 0);
-        vbuf[i] = make_uint4(0, 0, 0, 0);
-      }
+      int g = tile * BN + row;
+      g = g < n_total ? g : n_total - 1;
+      const bool prior = g < n_prior;
+      const long long off = static_cast<long long>(prior ? g : g - n_prior) * D128 + col * 8;
+      kbuf[i] = ldg16((prior ? k_prior : k_cur) + off);
+      vbuf[i] = ldg16((prior ? v_prior : v_cur) + off);
     }
   };
   auto store_tile = [&]() {
@@ -116,95 +130,135 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   const int tr_i = lane & 15, tr_grp = lane >> 4;
   const int tr_off = (4 * hl + (tr_i >> 2)) * VSTR + (tr_grp & 1) * 16 + 4 * (tr_i & 3);
 
-  load_tile(0);
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    __syncthreads();
-    store_tile();
-    __syncthreads();
-    if (tile + 1 < n_tiles) load_tile(tile + 1);
+  // The running reference m_run of a row is only raised when the tile maximum exceeds it by more than
+  // kSlack in the exponent (base 2): probabilities are then at most 2^kSlack, far inside fp32/bf16 range,
+  // the final division by the row sum makes the result independent of the reference, and the expensive
+  // rescaling of the accumulators happens a handful of times per row instead of every few tiles.
+  constexpr float kSlack = 8.f;
+  const float slack_raw = kSlack / c;
 
-    // S^T = K Q^T for the 64 keys of the tile x this wavefront's 32 queries.
-    f32x16 s[2];
+  auto process_tile = [&](auto masked, int left) {
+    // S^T = K Q^T for the 64 keys of the tile x this wavefront's 32*NB queries.
+    f32x16 s[NB][2];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[nb][cb][r] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(32 * cb + n) * KSTR + 16 * ks + 8 * hl]);
-        s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[cb], 0, 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          s[nb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[nb][ks], s[nb][cb], 0, 0, 0);
       }
+    // s[nb][cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query block nb, column n.
+    if constexpr (decltype(masked)::value) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[nb][cb][r] = -INFINITY;
     }
-    // s[cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query n.
-    if (tile == n_tiles - 1) {
-      const int left = n_total - tile * BN;
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
-    mx = fmaxf(mx, swap_halves(mx));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = fast_exp2((m_run - m_new) * c);
-    const float mc = m_new * c;
-    m_run = m_new;
-    float rowsum = 0.f;
-    bf16x8 pb[2][2];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = fast_exp2(fmaf(s[cb][r], c, -mc));
-        rowsum += e;
-        pb[cb][r >> 3][r & 7] = static_cast<bf16_t>(e);
-      }
-    l_run = fmaf(l_run, alpha, rowsum);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
 
-    // O^T += V^T P^T.
+    float mc[NB];
+    bool raise = false;
+    float mx[NB];
 #pragma unroll
-    for (int dblk = 0; dblk < 4; ++dblk)
+    for (int nb = 0; nb < NB; ++nb) {
+      float m = s[nb][0][0];
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, s[nb][cb][r]);
+      mx[nb] = max_halves(m);
+      raise = raise || (mx[nb] > m_run[nb] + slack_raw);
+    }
+    if (__any(raise)) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const float m_new = fmaxf(m_run[nb], mx[nb]);
+        const float alpha = fast_exp2((m_run[nb] - m_new) * c);
+        m_run[nb] = m_new;
+        l_run[nb] *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[nb][i][r] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) mc[nb] = m_run[nb] * c;
+
+    // P^T = 2^(S^T c - m c) in bf16, 16 keys at a time, each chunk feeding O^T += V^T P^T at once.
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 pb[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          float part = 0.f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float e = fast_exp2(fmaf(s[nb][cb][8 * ks + j], c, -mc[nb]));
+            part += e;
+            pb[nb][j] = static_cast<bf16_t>(e);
+          }
+          l_run[nb] += part;
+        }
+#pragma unroll
+        for (int dblk = 0; dblk < 4; ++dblk) {
           const bf16_t* base = &Vs[(32 * cb + 16 * ks) * VSTR + dblk * 32 + tr_off];
-          const s16x4 lo = lds_read_tr16(base);
-          const s16x4 hi = lds_read_tr16(base + 8 * VSTR);
           union {
             struct {
               s16x4 lo, hi;
             } s;
             bf16x8 v;
           } a;
-          a.s.lo = lo;
-          a.s.hi = hi;
-          o[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb[cb][ks], o[dblk], 0, 0, 0);
+          a.s.lo = lds_read_tr16(base);
+          a.s.hi = lds_read_tr16(base + 8 * VSTR);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            o[nb][dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb[nb], o[nb][dblk], 0, 0, 0);
         }
-  }
-
-  const float l_tot = l_run + swap_halves(l_run);
-  const float inv = 1.f / l_tot;
-  if (q_row < t_k) {
-    bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(q_row) * D128;
-#pragma unroll
-    for (int dblk = 0; dblk < 4; ++dblk)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + dblk * 32 + 8 * g + 4 * hl) = v;
       }
+  };
+
+  load_tile(0);
+  for (int tile = 0; tile < n_tiles - 1; ++tile) {
+    __syncthreads();
+    store_tile();
+    __syncthreads();
+    load_tile(tile + 1);
+    process_tile(std::false_type{}, BN);
+  }
+  __syncthreads();
+  store_tile();
+  __syncthreads();
+  process_tile(std::true_type{}, n_total - (n_tiles - 1) * BN);
+
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const float l_tot = sum_halves(l_run[nb]);
+    const float inv = 1.f / l_tot;
+    if (q_row[nb] < t_k) {
+      bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(q_row[nb]) * D128;
+#pragma unroll
+      for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[nb][dblk][4 * g + e] * inv);
+          *reinterpret_cast<bf16x4*>(op + dblk * 32 + 8 * g + 4 * hl) = v;
+        }
+    }
   }
 }
 
@@ -331,9 +385,16 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   p.sm_scale = a.sm_scale;
   if (a.dtype == HEATKV_BF16) {
     if (a.d != 128) return hipErrorInvalidValue;
-    p.n_qtiles = (a.t_k + BM - 1) / BM;
-    const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
-    hipLaunchKernelGGL(attend_bf16_d128_kernel, dim3(grid), dim3(256), 0, stream, p);
+    // 256-query workgroups once they still fill the chip; 128-query workgroups for the short scales.
+    const long long wide_groups = static_cast<long long>((a.t_k + 255) / 256) * a.H * a.batch;
+    if (wide_groups >= 256) {
+      p.n_qtiles = (a.t_k + 255) / 256;
+      hipLaunchKernelGGL(attend_bf16_d128_kernel<2>, dim3(unsigned(wide_groups)), dim3(256), 0, stream, p);
+    } else {
+      p.n_qtiles = (a.t_k + 127) / 128;
+      const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
+      hipLaunchKernelGGL(attend_bf16_d128_kernel<1>, dim3(grid), dim3(256), 0, stream, p);
+    }
   } else {
     p.n_qtiles = (a.t_k + FQ - 1) / FQ;
     const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;

@@ -22,6 +22,29 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Value of lane (l ^ 32): the partner in the other half of the wavefront.
 __device__ __forceinline__ float swap_halves(float v) { return __shfl_xor(v, 32, 64); }
 
+// Reductions over the two halves of a wavefront (lane l with lane l ^ 32) with one v_permlane32_swap.
+// The instruction exchanges the upper half of its first register with the lower half of its second, in
+// place; fed two copies of v it leaves {lower-half values on all lanes, upper-half values on all lanes}.
+// It is issued through inline assembly with two read-write operands: the compiler builtin of this
+// toolchain folds its two results into one register.  The leading s_nop covers the wait states the
+// instruction needs after a vector-ALU write of its operands.
+__device__ __forceinline__ void split_halves(float v, float& lower, float& upper) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  lower = a;
+  upper = b;
+}
+__device__ __forceinline__ float max_halves(float v) {
+  float a, b;
+  split_halves(v, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_halves(float v) {
+  float a, b;
+  split_halves(v, a, b);
+  return a + b;
+}
+
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
 // A 64-bit LDS read that transposes 16-bit elements inside each group of 16
