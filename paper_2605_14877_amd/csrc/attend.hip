@@ -6,6 +6,7 @@
 // the current scale.  Both kernels walk this virtual key sequence in tiles,
 // keep running row maxima and row sums in fp32 (online softmax) and normalise
 // once at the end.
+#include <cstdlib>
 #include <type_traits>
 
 #include "device_util.h"
@@ -30,235 +31,262 @@ struct AttendParams {
 // ---------------------------------------------------------------------------
 // bf16, d = 128: matrix-core kernel.
 //
-// Workgroup = 4 wavefronts, 128 queries (32 per wavefront); key tiles of 64
-// rows are staged row-major in LDS.  Scores are produced transposed,
-// S^T = K Q^T, with v_mfma_f32_32x32x16_bf16 so that one lane owns one query
-// column: row maxima and sums are in-register reductions plus one exchange
-// between the two wavefront halves, and the probabilities, rounded to bf16,
-// already sit in the B-operand layout of the second product O^T += V^T P^T.
-// V^T is read out of the row-major LDS tile with the transposing LDS read.
+// Workgroup = 4 wavefronts x 32 queries, two workgroups per compute unit.  The
+// keys of a head are walked in 64-row tiles, first the current scale (dense
+// tensor), then the head's retained run in the arena (attention does not depend
+// on key order, and each segment is then one contiguous range, so a tile's
+// addresses are a wavefront-uniform base plus a fixed per-lane offset).
+//
+// Tiles go from HBM straight into LDS (global_load_lds, no registers, no LDS
+// store instructions), double-buffered with one barrier per tile.  A tile is
+// stored row-major, 256 bytes per row, unpadded; the 16-byte chunks of a row are
+// XOR-swizzled with the row number (the lane that fills an LDS slot simply
+// fetches the matching global chunk) so that both read patterns below are free of
+// bank conflicts.
+//
+// Scores are produced transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: K
+// rows are the A operand straight from LDS, Q stays in registers as the B operand.
+// One lane then owns one query column: row maxima and sums are in-register
+// reductions plus one exchange between the wavefront halves, and the bf16
+// probabilities already sit in the B-operand layout of O^T += V^T P^T.  V^T comes
+// out of the row-major V tile with the transposing LDS read; the order of keys
+// inside a 16-key MFMA step is permuted identically on both operands.
 // ---------------------------------------------------------------------------
-constexpr int BN = 64;     // keys per tile
+constexpr int BM = 128;              // queries per workgroup
+constexpr int BN = 64;               // keys per tile
 constexpr int D128 = 128;
-constexpr int KSTR = 136;  // LDS row stride of the K tile in elements (272 B: conflict-free 16-byte row reads)
-constexpr int VSTR = 160;  // LDS row stride of the V tile in elements (320 B: best for the transposing read)
+constexpr int ROW_BYTES = 256;       // one bf16 row
+constexpr int TILE_BYTES = BN * ROW_BYTES;
 
-// NB = 32-query blocks per wavefront.  NB = 2 (256 queries per workgroup, one
-// wavefront per SIMD, up to 512 registers) halves the LDS traffic per flop: every
-// K or V operand fetched from LDS feeds two matrix instructions.  NB = 1 (128
-// queries per workgroup, two wavefronts per SIMD) keeps more workgroups in
-// flight for the short scales.
-template <int NB>
-__global__ __launch_bounds__(256, (NB == 1 ? 2 : 1)) void attend_bf16_d128_kernel(AttendParams p) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[BN * KSTR];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[BN * VSTR];
-  constexpr int BM = 128 * NB;  // queries per workgroup
+// Chunk swizzle: 8 consecutive rows map to 8 distinct values (16-byte row reads of the K operand), and 4
+// consecutive rows starting at a multiple of 4 map to values two apart (32-byte accesses of the V read).
+__device__ __forceinline__ int swizzle_of_row(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+__global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[2][2][TILE_BYTES];  // [buffer][K,V]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform, kept in a scalar register
   const int n = lane & 31, hl = lane >> 5;
 
-  int id = blockIdx.x;
-  const int qt = id % p.n_qtiles;
-  id /= p.n_qtiles;
-  const int b = id % p.batch;
-  const int h = p.head_order[id / p.batch];
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All query tiles of one
+  // (batch row, head) pair read the same K/V, so they are given ids that land on one XCD; pairs are dealt
+  // to XCDs in order of decreasing run length, which also balances the work between XCDs.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int pair = (slot / p.n_qtiles) * 8 + xcd;
+  if (pair >= p.H * p.batch) return;
+  const int qt = slot % p.n_qtiles;
+  const int b = pair % p.batch;
+  const int h = p.head_order[pair / p.batch];
 
   const int t_k = p.t_k;
   const int n_prior = p.run_len[h];
-  const int n_total = n_prior + t_k;
   const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D128;
   const long long run_off = (static_cast<long long>(b) * p.arena_tokens + p.run_row[h]) * D128;
-  const bf16_t* k_prior = static_cast<const bf16_t*>(p.k_arena) + run_off;
-  const bf16_t* v_prior = static_cast<const bf16_t*>(p.v_arena) + run_off;
-  const bf16_t* k_cur = static_cast<const bf16_t*>(p.k_cur) + cur_off;
-  const bf16_t* v_cur = static_cast<const bf16_t*>(p.v_cur) + cur_off;
+  const char* k_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_arena) + run_off);
+  const char* v_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_arena) + run_off);
+  const char* k_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_cur) + cur_off);
+  const char* v_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_cur) + cur_off);
 
-  // Q as B operand: lane (n, hl) holds Q[row][16*ks + 8*hl .. +7] for ks = 0..7, for each of its NB rows.
-  int q_row[NB];
-  bf16x8 qreg[NB][8];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    q_row[nb] = qt * BM + wave * (32 * NB) + 32 * nb + n;
-    const int ld = q_row[nb] < t_k ? q_row[nb] : t_k - 1;
+  // Q as B operand: lane (n, hl) holds Q[row][16*ks + 8*hl .. +7] for ks = 0..7.
+  const int q_row = qt * BM + wave * 32 + n;
+  bf16x8 qreg[8];
+  {
+    const int ld = q_row < t_k ? q_row : t_k - 1;
     const bf16_t* qp = static_cast<const bf16_t*>(p.q) + cur_off + static_cast<long long>(ld) * D128 + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
 
-  f32x16 o[NB][4];
-  float m_run[NB], l_run[NB];
+  // Tile schedule: tiles [0, tiles_cur) cover the current scale, the rest the retained run.
+  const int tiles_cur = (t_k + BN - 1) / BN;
+  const int tiles_all = tiles_cur + (n_prior + BN - 1) / BN;
+
+  // Loader: wavefront w fills LDS bytes [(4j + w) KB, +1 KB) of a tile with instruction j = 0..3, lane L
+  // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16, slot L % 16.
+  int ld_off[4];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    m_run[nb] = -INFINITY;
-    l_run[nb] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[nb][i][r] = 0.f;
+  for (int j = 0; j < 4; ++j) {
+    const int row = 4 * (4 * j + wave) + (lane >> 4);
+    ld_off[j] = row * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
   }
-  const float c = p.sm_scale * kLog2e;
-
-  const int n_tiles = (n_total + BN - 1) / BN;
-  uint4 kbuf[4], vbuf[4];
-
-  // Global -> register stage of the next tile.  Rows past the end of the key sequence re-read the last
-  // valid row (finite data); their scores are masked to -inf in the last tile, so they contribute nothing.
-  auto load_tile = [&](int tile) {
+  // The copy HBM -> LDS is issued as raw global_load_lds instructions: the compiler then does not see an
+  // LDS store it would have to order against the tile reads of the other buffer (it would wait for the
+  // whole prefetch in the middle of the math).  Ordering is explicit instead: s_waitcnt vmcnt(0) and the
+  // workgroup barrier at the top of every tile step.
+  const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<unsigned long long>(
+      (__attribute__((address_space(3))) char*)(&lds[0][0][0])));
+  auto issue_tile = [&](int it, int buf) {
+    const bool prior = it >= tiles_cur;
+    const int local = prior ? it - tiles_cur : it;
+    const int left = (prior ? n_prior : t_k) - local * BN;  // valid rows in this tile, >= 1
+    const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
+    const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i;
-      const int row = chunk >> 4, col = chunk & 15;
-      int g = tile * BN + row;
-      g = g < n_total ? g : n_total - 1;
-      const bool prior = g < n_prior;
-      const long long off = static_cast<long long>(prior ? g : g - n_prior) * D128 + col * 8;
-      kbuf[i] = ldg16((prior ? k_prior : k_cur) + off);
-      vbuf[i] = ldg16((prior ? v_prior : v_cur) + off);
-    }
-  };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i;
-      const int row = chunk >> 4, col = chunk & 15;
-      *reinterpret_cast<uint4*>(&Ks[row * KSTR + col * 8]) = kbuf[i];
-      *reinterpret_cast<uint4*>(&Vs[row * VSTR + col * 8]) = vbuf[i];
+    for (int j = 0; j < 4; ++j) {
+      int off = ld_off[j];
+      if (left < BN) {  // ragged tail: rows past the end re-read the last valid row (masked later)
+        const int row = 4 * (4 * j + wave) + (lane >> 4);
+        const int rr = row < left ? row : left - 1;
+        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+      }
+      const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + (4 * j + wave) * 1024;
+      const unsigned vd = kd + TILE_BYTES;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(kb) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd), "v"(off), "s"(vb) : "memory");
     }
   };
 
-  // Address pattern of the transposing V read (see lds_read_tr16).
+  // Reader offsets inside a tile.
+  int k_off[8];  // K operand: row n (+32 cb), chunk 2 ks + hl
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * ROW_BYTES + (((2 * ks + hl) ^ swizzle_of_row(n)) << 4);
+  // V operand through the transposing read: lane i of a 16-lane group points at row key0 + 4 hl + i / 4,
+  // columns 32 dblk + 16 (group & 1) + 4 (i % 4) .. +3, and receives column i of that 4 x 16 block.
   const int tr_i = lane & 15, tr_grp = lane >> 4;
-  const int tr_off = (4 * hl + (tr_i >> 2)) * VSTR + (tr_grp & 1) * 16 + 4 * (tr_i & 3);
+  const int v_row = 4 * hl + (tr_i >> 2);
+  int v_off[4];
+#pragma unroll
+  for (int dblk = 0; dblk < 4; ++dblk) {
+    const int chunk = 4 * dblk + 2 * (tr_grp & 1) + ((tr_i & 3) >> 1);
+    v_off[dblk] = v_row * ROW_BYTES + ((chunk ^ swizzle_of_row(v_row)) << 4) + ((tr_i & 1) << 3);
+  }
 
+  f32x16 o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = p.sm_scale * kLog2e;
   // The running reference m_run of a row is only raised when the tile maximum exceeds it by more than
   // kSlack in the exponent (base 2): probabilities are then at most 2^kSlack, far inside fp32/bf16 range,
   // the final division by the row sum makes the result independent of the reference, and the expensive
   // rescaling of the accumulators happens a handful of times per row instead of every few tiles.
   constexpr float kSlack = 8.f;
   const float slack_raw = kSlack / c;
+  const bf16x2 ones = {static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)};
 
-  auto process_tile = [&](auto masked, int left) {
-    // S^T = K Q^T for the 64 keys of the tile x this wavefront's 32*NB queries.
-    f32x16 s[NB][2];
+  // One tile: wait for its data, start the copy of the next tile into the other buffer, do the math.
+  // The buffer index is a template constant so that every LDS address is a register plus an immediate.
+  auto tile_step = [&](int it, auto buf_tag) {
+    constexpr int buf = decltype(buf_tag)::value;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + 1 < tiles_all) issue_tile(it + 1, buf ^ 1);
+    const char* kt = lds[buf][0];
+    const char* vt = lds[buf][1];
+
+    // S^T = K Q^T for the 64 keys of the tile x this wavefront's 32 queries.  All 16 K operands are
+    // requested from LDS before the first matrix instruction so that their latencies overlap; the two
+    // accumulator chains (keys 0-31, keys 32-63) are interleaved.
+    f32x16 s[2];
+    bf16x8 ka[2][8];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[nb][cb][r] = 0.f;
+        ka[cb][ks] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[ks]);
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(32 * cb + n) * KSTR + 16 * ks + 8 * hl]);
+      for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          s[nb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[nb][ks], s[nb][cb], 0, 0, 0);
-      }
-    // s[nb][cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query block nb, column n.
-    if constexpr (decltype(masked)::value) {
+    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+      for (int cb = 0; cb < 2; ++cb)
+        s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[ks], s[cb], 0, 0, 0);
+    // Pin the order: the 16 LDS reads first, then the 16 matrix instructions.
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    // s[cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query column n.
+    {
+      const bool prior = it >= tiles_cur;
+      const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
+      if (left < BN) {
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[nb][cb][r] = -INFINITY;
-    }
-
-    float mc[NB];
-    bool raise = false;
-    float mx[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      float m = s[nb][0][0];
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) m = fmaxf(m, s[nb][cb][r]);
-      mx[nb] = max_halves(m);
-      raise = raise || (mx[nb] > m_run[nb] + slack_raw);
-    }
-    if (__any(raise)) {
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const float m_new = fmaxf(m_run[nb], mx[nb]);
-        const float alpha = fast_exp2((m_run[nb] - m_new) * c);
-        m_run[nb] = m_new;
-        l_run[nb] *= alpha;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[nb][i][r] *= alpha;
+            if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
       }
     }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) mc[nb] = m_run[nb] * c;
-
-    // P^T = 2^(S^T c - m c) in bf16, 16 keys at a time, each chunk feeding O^T += V^T P^T at once.
+    float mx = s[0][0];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        bf16x8 pb[NB];
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
+    mx = max_halves(mx);
+    if (__any(mx > m_run + slack_raw)) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = fast_exp2((m_run - m_new) * c);
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          float part = 0.f;
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float e = fast_exp2(fmaf(s[nb][cb][8 * ks + j], c, -mc[nb]));
-            part += e;
-            pb[nb][j] = static_cast<bf16_t>(e);
-          }
-          l_run[nb] += part;
-        }
+        for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+    }
+    const float mc = m_run * c;
+
+    // P^T = 2^(S^T c - m c) in bf16, 16 keys at a time, each chunk feeding O^T += V^T P^T at once.  The V
+    // operands of a chunk are requested one chunk ahead of their use.  The row sum is taken over the
+    // rounded probabilities, pairwise, with the bf16 dot-product instruction.
+    union VOperand {
+      struct {
+        s16x4 lo, hi;
+      } s;
+      bf16x8 v;
+    };
+    auto read_v = [&](VOperand (&dst)[4], int chunk) {
 #pragma unroll
-        for (int dblk = 0; dblk < 4; ++dblk) {
-          const bf16_t* base = &Vs[(32 * cb + 16 * ks) * VSTR + dblk * 32 + tr_off];
-          union {
-            struct {
-              s16x4 lo, hi;
-            } s;
-            bf16x8 v;
-          } a;
-          a.s.lo = lds_read_tr16(base);
-          a.s.hi = lds_read_tr16(base + 8 * VSTR);
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            o[nb][dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, pb[nb], o[nb][dblk], 0, 0, 0);
-        }
+      for (int dblk = 0; dblk < 4; ++dblk) {
+        const char* base = vt + 16 * chunk * ROW_BYTES + v_off[dblk];
+        dst[dblk].s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
+        dst[dblk].s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
       }
-  };
-
-  load_tile(0);
-  for (int tile = 0; tile < n_tiles - 1; ++tile) {
-    __syncthreads();
-    store_tile();
-    __syncthreads();
-    load_tile(tile + 1);
-    process_tile(std::false_type{}, BN);
-  }
-  __syncthreads();
-  store_tile();
-  __syncthreads();
-  process_tile(std::true_type{}, n_total - (n_tiles - 1) * BN);
-
+    };
+    VOperand va[2][4];
+    read_v(va[0], 0);
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const float l_tot = sum_halves(l_run[nb]);
-    const float inv = 1.f / l_tot;
-    if (q_row[nb] < t_k) {
-      bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(q_row[nb]) * D128;
+    for (int chunk = 0; chunk < 4; ++chunk) {
+      if (chunk + 1 < 4) read_v(va[(chunk + 1) & 1], chunk + 1);
+      const int cb = chunk >> 1, ks = chunk & 1;
+      union {
+        bf16x8 v;
+        bf16x2 h[4];
+      } pb;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pb.v[j] = static_cast<bf16_t>(fast_exp2(fmaf(s[cb][8 * ks + j], c, -mc)));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) l_run = __builtin_amdgcn_fdot2_f32_bf16(pb.h[j], ones, l_run, false);
 #pragma unroll
       for (int dblk = 0; dblk < 4; ++dblk)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[nb][dblk][4 * g + e] * inv);
-          *reinterpret_cast<bf16x4*>(op + dblk * 32 + 8 * g + 4 * hl) = v;
-        }
+        o[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[chunk & 1][dblk].v, pb.v, o[dblk], 0, 0, 0);
     }
+  };
+
+  issue_tile(0, 0);
+  int it = 0;
+  for (; it + 1 < tiles_all; it += 2) {
+    tile_step(it, std::integral_constant<int, 0>{});
+    tile_step(it + 1, std::integral_constant<int, 1>{});
+  }
+  if (it < tiles_all) tile_step(it, std::integral_constant<int, 0>{});
+
+  const float l_tot = sum_halves(l_run);
+  const float inv = 1.f / l_tot;
+  if (q_row < t_k) {
+    bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(q_row) * D128;
+#pragma unroll
+    for (int dblk = 0; dblk < 4; ++dblk)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + dblk * 32 + 8 * g + 4 * hl) = v;
+      }
   }
 }
 
@@ -385,16 +413,10 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   p.sm_scale = a.sm_scale;
   if (a.dtype == HEATKV_BF16) {
     if (a.d != 128) return hipErrorInvalidValue;
-    // 256-query workgroups once they still fill the chip; 128-query workgroups for the short scales.
-    const long long wide_groups = static_cast<long long>((a.t_k + 255) / 256) * a.H * a.batch;
-    if (wide_groups >= 256) {
-      p.n_qtiles = (a.t_k + 255) / 256;
-      hipLaunchKernelGGL(attend_bf16_d128_kernel<2>, dim3(unsigned(wide_groups)), dim3(256), 0, stream, p);
-    } else {
-      p.n_qtiles = (a.t_k + 127) / 128;
-      const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
-      hipLaunchKernelGGL(attend_bf16_d128_kernel<1>, dim3(grid), dim3(256), 0, stream, p);
-    }
+    p.n_qtiles = (a.t_k + BM - 1) / BM;
+    const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
+    const unsigned grid = unsigned(p.n_qtiles) * pairs8;
+    hipLaunchKernelGGL(attend_bf16_d128_kernel, dim3(grid), dim3(256), 0, stream, p);
   } else {
     p.n_qtiles = (a.t_k + FQ - 1) / FQ;
     const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
