@@ -71,9 +71,10 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All query tiles of one
   // (batch row, head) pair read the same K/V, so they are given ids that land on one XCD; pairs are dealt
-  // to XCDs in order of decreasing run length, which also balances the work between XCDs.
+  // to XCDs in order of decreasing run length, alternating direction, which balances the work between XCDs.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int pair = (slot / p.n_qtiles) * 8 + xcd;
+  const int turn = slot / p.n_qtiles;  // pairs are dealt to the XCDs back and forth (0..7, 7..0, 0..7, ...)
+  const int pair = turn * 8 + ((turn & 1) ? 7 - xcd : xcd);
   if (pair >= p.H * p.batch) return;
   const int qt = slot % p.n_qtiles;
   const int b = pair % p.batch;

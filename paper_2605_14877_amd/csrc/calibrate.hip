@@ -11,6 +11,8 @@
 // summed over the workgroup's rows in a fixed order and written as one partial
 // per (head, query tile); a second kernel adds the partials in tile order, so
 // the result is bit-reproducible (no floating-point atomics anywhere).
+#include <type_traits>
+
 #include "device_util.h"
 #include "kernels.h"
 
@@ -32,112 +34,156 @@ struct CalibParams {
 
 // ---------------------------------------------------------------------------
 // bf16, d = 128: S^T = K Q^T on the matrix cores, one lane per query column
-// (same operand layout as the attention kernel), 128 queries per workgroup.
+// (same operand layout, LDS tile format and HBM -> LDS copy as the attention
+// kernel), 128 queries per workgroup, up to three workgroups per compute unit.
 // ---------------------------------------------------------------------------
 constexpr int CBM = 128;
 constexpr int CBN = 64;
 constexpr int CD = 128;
-constexpr int CKSTR = 136;
+constexpr int CROW_BYTES = 256;
+constexpr int CTILE_BYTES = CBN * CROW_BYTES;
 
-__global__ __launch_bounds__(256, 2) void calibrate_bf16_d128_kernel(CalibParams p) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[CBN * CKSTR];
-  __shared__ float blk_sum[MAXK][CBM];
-  __shared__ float blk_max[MAXK][CBM];
-  __shared__ float fin_max[CBM];
+__device__ __forceinline__ int swizzle_of_row(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+// Dynamic LDS: two K tiles, then blk_sum[k1+1][128], blk_max[k1+1][128], fin_max[128] (floats).
+__host__ __device__ constexpr size_t calib_lds_bytes(int k1) {
+  return 2 * CTILE_BYTES + (2 * size_t(k1 + 1) + 1) * CBM * sizeof(float);
+}
+
+__global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int k1 = p.k1, t_k1 = p.t_k1;
+  float* blk_sum = reinterpret_cast<float*>(lds + 2 * CTILE_BYTES);
+  float* blk_max = blk_sum + (k1 + 1) * CBM;
+  float* fin_max = blk_max + (k1 + 1) * CBM;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hl = lane >> 5;
-  int id = blockIdx.x;
-  const int qt = id % p.n_qtiles;
-  const int bh = id / p.n_qtiles;
-  const int t_k1 = p.t_k1, k1 = p.k1;
+
+  // All query tiles of one (batch row, head) read the same keys: give them ids on one XCD (id % 8).
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int bh = (slot / p.n_qtiles) * 8 + xcd;
+  if (bh >= p.batch * p.H) return;
+  const int qt = slot % p.n_qtiles;
   const int c_k1 = p.c[k1];
 
-  const bf16_t* kbase = static_cast<const bf16_t*>(p.k_all) + static_cast<long long>(bh) * c_k1 * CD;
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_all) +
+                                                    static_cast<long long>(bh) * c_k1 * CD);
   const int q_row = qt * CBM + wave * 32 + n;
-  const int q_row_ld = q_row < t_k1 ? q_row : t_k1 - 1;
   bf16x8 qreg[8];
   {
-    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + (static_cast<long long>(bh) * t_k1 + q_row_ld) * CD + 8 * hl;
+    const int ld = q_row < t_k1 ? q_row : t_k1 - 1;
+    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + (static_cast<long long>(bh) * t_k1 + ld) * CD + 8 * hl;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
   const float c = p.sm_scale * kLog2e;
-  float m_run = -INFINITY;
 
-  uint4 kbuf[4];
-  auto load_tile = [&](int k2, int tile) {
-    const int first = p.c[k2] - p.t[k2] + tile * CBN;
-    const int left = p.t[k2] - tile * CBN;
+  // HBM -> LDS copy of one tile (see the attention kernel: raw global_load_lds, explicit ordering).
+  int ld_off[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i;
-      const int row = chunk >> 4, col = chunk & 15;
-      kbuf[i] = row < left ? ldg16(kbase + static_cast<long long>(first + row) * CD + col * 8) : make_uint4(0, 0, 0, 0);
+  for (int j = 0; j < 4; ++j) {
+    const int row = 4 * (4 * j + wave) + (lane >> 4);
+    ld_off[j] = row * CROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+  }
+  const unsigned lds_base =
+      static_cast<unsigned>(reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0])));
+  auto issue_tile = [&](int k2, int tile, int buf) {
+    const int left = p.t[k2] - tile * CBN;
+    const char* kb = kbase + static_cast<long long>(p.c[k2] - p.t[k2] + tile * CBN) * CROW_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int off = ld_off[j];
+      if (left < CBN) {
+        const int row = 4 * (4 * j + wave) + (lane >> 4);
+        const int rr = row < left ? row : left - 1;
+        off = rr * CROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+      }
+      const unsigned kd = lds_base + buf * CTILE_BYTES + (4 * j + wave) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(kb) : "memory");
     }
   };
+  int k_off[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * CROW_BYTES + (((2 * ks + hl) ^ swizzle_of_row(n)) << 4);
 
-  int k2 = 0, tile = 0;
-  load_tile(0, 0);
-  while (k2 <= k1) {
-    float cur = 0.f;
+  float m_run = -INFINITY, cur = 0.f;
+  int k2 = 0, tile = 0;  // the tile being computed
+
+  auto tile_step = [&](auto buf_tag) {
+    constexpr int buf = decltype(buf_tag)::value;
+    // successor of (k2, tile) in block-major order
     const int tiles_here = (p.t[k2] + CBN - 1) / CBN;
-    for (; tile < tiles_here; ++tile) {
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int chunk = tid + 256 * i;
-        *reinterpret_cast<uint4*>(&Ks[(chunk >> 4) * CKSTR + (chunk & 15) * 8]) = kbuf[i];
-      }
-      __syncthreads();
-      if (tile + 1 < tiles_here)
-        load_tile(k2, tile + 1);
-      else if (k2 + 1 <= k1)
-        load_tile(k2 + 1, 0);
+    const bool last_of_block = tile + 1 >= tiles_here;
+    const int nk2 = last_of_block ? k2 + 1 : k2, ntile = last_of_block ? 0 : tile + 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (nk2 <= k1) issue_tile(nk2, ntile, buf ^ 1);
+    const char* kt = lds + buf * CTILE_BYTES;
 
-      f32x16 s[2];
+    f32x16 s[2];
+    bf16x8 ka[2][8];
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
+    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
+      for (int cb = 0; cb < 2; ++cb)
+        ka[cb][ks] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * CROW_BYTES + k_off[ks]);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(32 * cb + n) * CKSTR + 16 * ks + 8 * hl]);
-          s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[cb], 0, 0, 0);
-        }
-      }
-      const int left = p.t[k2] - tile * CBN;
-      if (left < CBN) {
+    for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+      for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
-      }
-      float mx = s[0][0];
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+        s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[ks], s[cb], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+
+    const int left = p.t[k2] - tile * CBN;
+    if (left < CBN) {
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
-      mx = fmaxf(mx, swap_halves(mx));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = fast_exp2((m_run - m_new) * c);
-      const float mc = m_new * c;
-      m_run = m_new;
-      float rowsum = 0.f;
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) rowsum += fast_exp2(fmaf(s[cb][r], c, -mc));
-      cur = fmaf(cur, alpha, rowsum);
+        for (int r = 0; r < 16; ++r)
+          if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
     }
-    const float both = cur + swap_halves(cur);
-    if (hl == 0) {
-      blk_sum[k2][wave * 32 + n] = both;
-      blk_max[k2][wave * 32 + n] = m_run;
+    float mx = s[0][0];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
+    mx = max_halves(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = fast_exp2((m_run - m_new) * c);
+    const float mc = m_new * c;
+    m_run = m_new;
+    float rs[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) rs[r & 3] += fast_exp2(fmaf(s[cb][r], c, -mc));
+    cur = fmaf(cur, alpha, (rs[0] + rs[1]) + (rs[2] + rs[3]));
+
+    if (last_of_block) {
+      const float both = sum_halves(cur);
+      if (hl == 0) {
+        blk_sum[k2 * CBM + wave * 32 + n] = both;
+        blk_max[k2 * CBM + wave * 32 + n] = m_run;
+      }
+      cur = 0.f;
     }
-    ++k2;
-    tile = 0;
+    k2 = nk2;
+    tile = ntile;
+  };
+
+  issue_tile(0, 0, 0);
+  while (true) {
+    tile_step(std::integral_constant<int, 0>{});
+    if (k2 > k1) break;
+    tile_step(std::integral_constant<int, 1>{});
+    if (k2 > k1) break;
   }
   if (hl == 0) fin_max[wave * 32 + n] = m_run;
   __syncthreads();
@@ -147,16 +193,16 @@ __global__ __launch_bounds__(256, 2) void calibrate_bf16_d128_kernel(CalibParams
     const float mf = fin_max[tid];
     float l = 0.f;
     for (int j = 0; j <= k1; ++j) {
-      const float w = blk_sum[j][tid] * fast_exp2((blk_max[j][tid] - mf) * c);
-      blk_sum[j][tid] = w;
+      const float w = blk_sum[j * CBM + tid] * fast_exp2((blk_max[j * CBM + tid] - mf) * c);
+      blk_sum[j * CBM + tid] = w;
       l += w;
     }
     const float inv = (qt * CBM + tid < t_k1) ? 1.f / l : 0.f;
-    for (int j = 0; j <= k1; ++j) blk_sum[j][tid] *= inv;
+    for (int j = 0; j <= k1; ++j) blk_sum[j * CBM + tid] *= inv;
   }
   __syncthreads();
   for (int j = wave; j <= k1; j += 4) {
-    float v = blk_sum[j][lane] + blk_sum[j][lane + 64];
+    float v = blk_sum[j * CBM + lane] + blk_sum[j * CBM + lane + 64];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
     if (lane == 0) p.partial[(static_cast<long long>(bh) * p.n_qtiles + qt) * p.K + j] = v;
@@ -304,7 +350,9 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
   const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
   if (a.dtype == HEATKV_BF16) {
     if (a.d != 128) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(calibrate_bf16_d128_kernel, dim3(grid), dim3(256), 0, stream, p);
+    const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
+    hipLaunchKernelGGL(calibrate_bf16_d128_kernel, dim3(unsigned(p.n_qtiles) * pairs8), dim3(256),
+                       calib_lds_bytes(a.k1), stream, p);
   } else if (a.d == 64) {
     hipLaunchKernelGGL(calibrate_f32_kernel<64>, dim3(grid), dim3(256), 0, stream, p);
   } else if (a.d == 128) {
