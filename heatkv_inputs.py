@@ -162,3 +162,35 @@ def explicit_keep_pattern(seed, L, H, t, budget):
     for k in range(K):
         present[k, :, :, :k] = keep[:, :, :k]
     return present
+
+
+def make_qkv_device(seed, layer, cfg, w, device, sm_scale=None, batch=None):
+    """Same recipe as make_qkv, drawn with torch's generator on `device` (for the full-size configs).
+
+    Returns Q, K, V as device tensors [batch, H, c_K, d] in the config dtype.  The values differ from
+    make_qkv's for the same seed (another generator); callers copy what they need back to the host.
+    """
+    H, d = cfg["H"], cfg["d"]
+    t = tokens_per_scale(cfg["sides"])
+    c = cumulative_tokens(t)
+    K = len(t)
+    nb = cfg["batch"] if batch is None else batch
+    if sm_scale is None:
+        sm_scale = 1.0 / np.sqrt(d)
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) * 1000003 + int(layer) * 7919 + 17)
+    td = torch_dtype(cfg["dtype"])
+    out = []
+    for _ in range(3):
+        out.append(torch.randn((nb, H, c[-1], d), generator=g, device=device, dtype=torch.float32))
+    q, k, v = out
+    if w is not None:
+        r0 = d - K
+        q[..., r0:] = 0.0
+        k[..., r0:] = 0.0
+        lw = torch.from_numpy(np.log(w[layer]) / sm_scale).to(device=device, dtype=torch.float32)  # [H, K]
+        for i in range(K):
+            k[:, :, c[i] - t[i]:c[i], r0 + i] = 1.0
+            if i + 1 < K:
+                q[:, :, c[i]:, r0 + i] = lw[None, :, i, None]
+    return tuple(x.to(td) for x in (q, k, v))
