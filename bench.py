@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--workload", default="layer2b", choices=["layer2b", "serving_layer", "layer8b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend-only", action="store_true", help="profiling aid: skip calibrate/schedule in the step")
+    ap.add_argument("--copy-probe-mb", type=int, default=0,
+                    help="profiling aid: after the timed region run one plain device copy of this many MiB "
+                         "(a kernel of known HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -203,6 +206,12 @@ def main():
         },
     }
 
+    if args.copy_probe_mb:
+        src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(q, k, v, t0, plan, sm, d)
     print(json.dumps(result))
