@@ -29,6 +29,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+# HBM bytes per attend launch (average over the 13 launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
+# scaled by a plain copy of known size; see profiles/attend_layer2b_hbm_traffic.txt.  Other workloads: not measured.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"layer2b": 38.8e6}
 
 
 def main():
@@ -199,7 +202,8 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+            "algorithmic_bytes_per_launch": round(sum(att_bytes) / K),
             "flops_per_step": sum(att_flops),
             "launches_per_step": K,
             "avg_launch_ms": round(total_att_ms / K, 4),
