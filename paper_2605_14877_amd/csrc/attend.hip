@@ -111,33 +111,12 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
     const int row = 4 * (4 * j + wave) + (lane >> 4);
     ld_off[j] = row * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
   }
-  // The copy HBM -> LDS is issued as raw global_load_lds instructions: the compiler then does not see an
-  // LDS store it would have to order against the tile reads of the other buffer (it would wait for the
-  // whole prefetch in the middle of the math).  Ordering is explicit instead: s_waitcnt vmcnt(0) and the
-  // workgroup barrier at the top of every tile step.
+  // The copy HBM -> LDS is issued as raw global_load_lds instructions (issue_k / issue_v below): the
+  // compiler then does not see an LDS store it would have to order against the tile reads of the other
+  // buffer (it would wait for the whole prefetch in the middle of the math).  Ordering is explicit
+  // instead: s_waitcnt vmcnt(0) and the workgroup barrier at the top of every tile step.
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<unsigned long long>(
       (__attribute__((address_space(3))) char*)(&lds[0][0][0])));
-  auto issue_tile = [&](int it, int buf) {
-    const bool prior = it >= tiles_cur;
-    const int local = prior ? it - tiles_cur : it;
-    const int left = (prior ? n_prior : t_k) - local * BN;  // valid rows in this tile, >= 1
-    const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
-    const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int off = ld_off[j];
-      if (left < BN) {  // ragged tail: rows past the end re-read the last valid row (masked later)
-        const int row = 4 * (4 * j + wave) + (lane >> 4);
-        const int rr = row < left ? row : left - 1;
-        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
-      }
-      const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + (4 * j + wave) * 1024;
-      const unsigned vd = kd + TILE_BYTES;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(kb) : "memory");
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd), "v"(off), "s"(vb) : "memory");
-    }
-  };
-
   // Reader offsets inside a tile.
   int k_off[8];  // K operand: row n (+32 cb), chunk 2 ks + hl
 #pragma unroll
@@ -168,26 +147,50 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   const float slack_raw = kSlack / c;
   const bf16x2 ones = {static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)};
 
-  // One tile: wait for its data, start the copy of the next tile into the other buffer, do the math.
-  // The buffer index is a template constant so that every LDS address is a register plus an immediate.
-  auto tile_step = [&](int it, auto buf_tag) {
-    constexpr int buf = decltype(buf_tag)::value;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (it + 1 < tiles_all) issue_tile(it + 1, buf ^ 1);
-    const char* kt = lds[buf][0];
-    const char* vt = lds[buf][1];
+  // ---- software-pipelined tile loop --------------------------------------------------------------
+  // Step `it` computes the scores of tile it+1 (matrix cores) while it turns the scores of tile `it` into
+  // probabilities (vector ALU) and accumulates P V for tile `it`.  K tiles are therefore fetched one tile
+  // further ahead than V tiles: at the top of step `it` the copies K(it+1) and V(it) must have landed.
+  auto issue_k = [&](int it, int buf) {
+    const bool prior = it >= tiles_cur;
+    const int local = prior ? it - tiles_cur : it;
+    const int left = (prior ? n_prior : t_k) - local * BN;
+    const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int off = ld_off[j];
+      if (left < BN) {
+        const int row = 4 * (4 * j + wave) + (lane >> 4);
+        const int rr = row < left ? row : left - 1;
+        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+      }
+      const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + (4 * j + wave) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(kb) : "memory");
+    }
+  };
+  auto issue_v = [&](int it, int buf) {
+    const bool prior = it >= tiles_cur;
+    const int local = prior ? it - tiles_cur : it;
+    const int left = (prior ? n_prior : t_k) - local * BN;
+    const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int off = ld_off[j];
+      if (left < BN) {
+        const int row = 4 * (4 * j + wave) + (lane >> 4);
+        const int rr = row < left ? row : left - 1;
+        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+      }
+      const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES + (4 * j + wave) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd), "v"(off), "s"(vb) : "memory");
+    }
+  };
 
-    // S^T = K Q^T for the 64 keys of the tile x this wavefront's 32 queries.  All 16 K operands are
-    // requested from LDS before the first matrix instruction so that their latencies overlap; the two
-    // accumulator chains (keys 0-31, keys 32-63) are interleaved.
-    f32x16 s[2];
-    bf16x8 ka[2][8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-        ka[cb][ks] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[ks]);
+  // S^T = K Q^T for the 64 keys of the K tile in buffer `buf` x this wavefront's 32 queries.
+  // s[cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query column n.
+  auto scores = [&](f32x16 (&s)[2], auto buf_tag) {
+    constexpr int buf = decltype(buf_tag)::value;
+    const char* kt = lds[buf][0];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -195,22 +198,22 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-        s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[ks], s[cb], 0, 0, 0);
-    // Pin the order: the 16 LDS reads first, then the 16 matrix instructions.
-    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-    // s[cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query column n.
-    {
-      const bool prior = it >= tiles_cur;
-      const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
-      if (left < BN) {
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
+      for (int cb = 0; cb < 2; ++cb) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[ks]);
+        s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[cb], 0, 0, 0);
       }
+  };
+  // Masks the ragged tail of tile `it`, folds its row maxima into the running reference and, rarely,
+  // rescales what has been accumulated so far.
+  auto settle = [&](int it, f32x16 (&s)[2]) {
+    const bool prior = it >= tiles_cur;
+    const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
+    if (left < BN) {
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
     }
     float mx = s[0][0];
 #pragma unroll
@@ -228,31 +231,29 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
     }
+  };
+  // P^T = 2^(S^T c - m c) in bf16, 16 keys at a time, each chunk feeding O^T += V^T P^T at once.  The row
+  // sum is taken over the rounded probabilities, pairwise, with the bf16 dot-product instruction.
+  union VOperand {
+    struct {
+      s16x4 lo, hi;
+    } s;
+    bf16x8 v;
+  };
+  auto accumulate = [&](const f32x16 (&s)[2], auto buf_tag) {
+    constexpr int buf = decltype(buf_tag)::value;
+    const char* vt = lds[buf][1];
     const float mc = m_run * c;
-
-    // P^T = 2^(S^T c - m c) in bf16, 16 keys at a time, each chunk feeding O^T += V^T P^T at once.  The V
-    // operands of a chunk are requested one chunk ahead of their use.  The row sum is taken over the
-    // rounded probabilities, pairwise, with the bf16 dot-product instruction.
-    union VOperand {
-      struct {
-        s16x4 lo, hi;
-      } s;
-      bf16x8 v;
-    };
-    auto read_v = [&](VOperand (&dst)[4], int chunk) {
+#pragma unroll
+    for (int chunk = 0; chunk < 4; ++chunk) {
+      const int cb = chunk >> 1, ks = chunk & 1;
+      VOperand va[4];
 #pragma unroll
       for (int dblk = 0; dblk < 4; ++dblk) {
         const char* base = vt + 16 * chunk * ROW_BYTES + v_off[dblk];
-        dst[dblk].s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
-        dst[dblk].s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
+        va[dblk].s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
+        va[dblk].s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
       }
-    };
-    VOperand va[2][4];
-    read_v(va[0], 0);
-#pragma unroll
-    for (int chunk = 0; chunk < 4; ++chunk) {
-      if (chunk + 1 < 4) read_v(va[(chunk + 1) & 1], chunk + 1);
-      const int cb = chunk >> 1, ks = chunk & 1;
       union {
         bf16x8 v;
         bf16x2 h[4];
@@ -263,17 +264,48 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
       for (int j = 0; j < 4; ++j) l_run = __builtin_amdgcn_fdot2_f32_bf16(pb.h[j], ones, l_run, false);
 #pragma unroll
       for (int dblk = 0; dblk < 4; ++dblk)
-        o[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[chunk & 1][dblk].v, pb.v, o[dblk], 0, 0, 0);
+        o[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dblk].v, pb.v, o[dblk], 0, 0, 0);
     }
   };
 
-  issue_tile(0, 0);
+  f32x16 s_cur[2], s_nxt[2];
+  // Steady-state step for tile `it` (it + 1 < tiles_all); K(it+1) sits in K buffer kb1, V(it) in V buffer vb0.
+  auto pipe_step = [&](int it, auto kb1, auto vb0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + 2 < tiles_all) issue_k(it + 2, decltype(vb0)::value);      // K buffer it & 1 was read by step it-1
+    issue_v(it + 1, decltype(kb1)::value);                              // V buffer (it+1) & 1 likewise
+    scores(s_nxt, kb1);
+    accumulate(s_cur, vb0);
+    settle(it + 1, s_nxt);
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) s_cur[cb] = s_nxt[cb];
+  };
+
+  // Prologue: K(0) alone, then its scores; K(1) and V(0) go out before the loop.
+  issue_k(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  scores(s_cur, std::integral_constant<int, 0>{});
+  settle(0, s_cur);
+  if (tiles_all > 1) issue_k(1, 1);
+  issue_v(0, 0);
   int it = 0;
-  for (; it + 1 < tiles_all; it += 2) {
-    tile_step(it, std::integral_constant<int, 0>{});
-    tile_step(it + 1, std::integral_constant<int, 1>{});
+  for (; it + 2 < tiles_all; it += 2) {
+    pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+    pipe_step(it + 1, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
   }
-  if (it < tiles_all) tile_step(it, std::integral_constant<int, 0>{});
+  if (it + 1 < tiles_all) {
+    pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+    ++it;
+  }
+  // Epilogue: the last tile has scores but no successor.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (it & 1)
+    accumulate(s_cur, std::integral_constant<int, 1>{});
+  else
+    accumulate(s_cur, std::integral_constant<int, 0>{});
 
   const float l_tot = sum_halves(l_run);
   const float inv = 1.f / l_tot;
