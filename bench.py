@@ -39,9 +39,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="layer2b", choices=["layer2b", "serving_layer", "layer8b"])
+    ap.add_argument("--workload", default="layer2b",
+                    choices=["layer2b", "serving_layer", "layer8b", "stack2b", "stack8b", "serving"],
+                    help="layer2b (default): one 2B-like layer, the whole path.  *_layer / layer8b: one layer of the "
+                         "named stack.  stack2b / stack8b / serving: every layer of the stack, generation-order "
+                         "attend + append only (schedule from a fabricated beta table, no calibration pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend-only", action="store_true", help="profiling aid: skip calibrate/schedule in the step")
+    ap.add_argument("--graph", action="store_true",
+                    help="stack workloads only: capture one generation pass in a HIP graph and time its replays")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="profiling aid: after the timed region run one plain device copy of this many MiB "
                          "(a kernel of known HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -61,6 +67,9 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
+    if args.workload in ("stack2b", "stack8b", "serving"):
+        run_stack(args, dev)
+        return
     base = {"layer2b": "layer2b", "serving_layer": "serving", "layer8b": "stack8b"}[args.workload]
     cfg = dict(hi.CONFIGS[base])
     cfg["L"] = 1  # one layer of the named stack: every attend/append/calibrate call is per layer
@@ -218,6 +227,101 @@ def main():
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(q, k, v, t0, plan, sm, d)
+    print(json.dumps(result))
+
+
+def run_stack(args, dev):
+    """Generation-order attend + append over every layer of a stack config (no calibration pass)."""
+    import torch
+
+    import heatkv_inputs as hi
+    import paper_2605_14877_amd as hk
+
+    cfg = hi.CONFIGS[args.workload]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    c = hi.cumulative_tokens(t0)
+    L, K, H, d, s, nb = cfg["L"], len(t0), cfg["H"], cfg["d"], cfg["sinks"], cfg["batch"]
+    esz = hi.elem_bytes(cfg["dtype"])
+    sm = 1.0 / np.sqrt(d)
+    B = hi.budget_tokens(cfg)
+    w = hi.head_weights(0, L, H, K)
+    beta = hi.expected_beta_from_weights(w, t0).astype(np.float32)
+    shape = hk.Shape(L, H, d, t0, nb, cfg["dtype"])
+    plan = hk.heatkv_build_schedule(shape, beta, B * 2 * d * esz, s)
+    plan.upload()
+    # one set of activations, reused by every layer (same shapes and value distribution; the plan differs per layer)
+    q, k, v = hi.make_qkv_device(0, 0, cfg, w, dev)
+    sl = [slice(c[i] - t0[i], c[i]) for i in range(K)]
+    q_s = [q[:, :, sl[i]].contiguous() for i in range(K)]
+    k_s = [k[:, :, sl[i]].contiguous() for i in range(K)]
+    v_s = [v[:, :, sl[i]].contiguous() for i in range(K)]
+    out_s = [torch.empty_like(x) for x in q_s]
+    del q, k, v
+    ka = torch.zeros(max(plan.arena_bytes, 16), dtype=torch.uint8, device=dev)
+    va = torch.zeros_like(ka)
+    flops = np.zeros(K)
+    byts = np.zeros(K)
+    for kk in range(K):
+        for l in range(L):
+            n = nb * int((plan.runs(kk, l)[1].astype(np.int64) + t0[kk]).sum())
+            flops[kk] += 4.0 * t0[kk] * d * n
+            byts[kk] += 2.0 * d * esz * (n + nb * H * t0[kk])
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+          for _ in range(args.steps)]
+
+    def step(i_timed=None):
+        for kk in range(K):
+            for l in range(L):
+                if i_timed is not None and l == 0:
+                    ev[i_timed][kk][0].record()
+                hk.heatkv_attend_scale(plan, l, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk])
+                hk.heatkv_append_scale(plan, l, kk, k_s[kk], v_s[kk], ka, va)
+            if i_timed is not None:
+                ev[i_timed][kk][1].record()
+
+    graph = None
+    if args.graph:
+        # The entry points only enqueue kernels once the plan is uploaded, so a whole pass can be captured.
+        step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        graph.replay() if graph else step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        graph.replay() if graph else step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
+    if graph:  # no per-scale events inside a graph: one eager pass supplies the per-scale split
+        step(0)
+        torch.cuda.synchronize()
+        scale_ms = np.array([a.elapsed_time(b) for a, b in ev[0]])
+    else:
+        scale_ms = np.array([[a.elapsed_time(b) for a, b in row] for row in ev]).mean(0)  # attend + append, L layers
+    value = flops.sum() / (ms_per_step * 1e-3) / 1e12
+    result = {
+        "metric": "attend_scale algorithmic TFLOP/s over generation-order attend + append of the whole stack",
+        "value": round(float(value), 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {L} layers x {H} heads x d{d} {cfg['dtype']}, batch {nb}, {K} scales, "
+                               f"{cfg['factor']}x budget, sinks {s}; schedule from a fabricated beta table; "
+                               f"attend + append only", "hip_graph": bool(args.graph)},
+        "per_image_attention_ms": round(ms_per_step / max(nb // 2, 1), 4),
+        "kv_cache_budget_mb": round(nb * B * 2 * d * esz / 1e6, 1),
+        "arena_mb": round(2 * plan.arena_bytes / 1e6, 1),
+        "arena_tokens_over_budget": round(plan.arena_tokens / B, 4),
+        "per_scale": [{"k": kk, "t": t0[kk], "ms": round(float(scale_ms[kk]), 4),
+                       "tflops": round(flops[kk] / (scale_ms[kk] * 1e-3) / 1e12, 2),
+                       "gbs": round(byts[kk] / (scale_ms[kk] * 1e-3) / 1e9, 1)} for kk in range(K)],
+        "roofline": {"kernel": "attend_bf16_d128_kernel (+ append_kernel inside the timed pairs)", "bound": "mfma",
+                     "achieved": round(float(value), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(float(value) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }
     print(json.dumps(result))
 
 
