@@ -46,6 +46,8 @@ def main():
                          "attend + append only (schedule from a fabricated beta table, no calibration pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend-only", action="store_true", help="profiling aid: skip calibrate/schedule in the step")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="call heatkv_attend_scale and heatkv_append_scale separately instead of the fused entry point")
     ap.add_argument("--graph", action="store_true",
                     help="stack workloads only: capture one generation pass in a HIP graph and time its replays")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
@@ -139,10 +141,16 @@ def main():
         for kk in range(K):
             if i_timed is not None:
                 ev[i_timed][kk][0].record()
-            hk.heatkv_attend_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk], att_ws[kk])
-            if i_timed is not None:
-                ev[i_timed][kk][1].record()
-            hk.heatkv_append_scale(plan, 0, kk, k_s[kk], v_s[kk], ka, va)
+            if args.separate_append:
+                hk.heatkv_attend_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk], att_ws[kk])
+                if i_timed is not None:
+                    ev[i_timed][kk][1].record()
+                hk.heatkv_append_scale(plan, 0, kk, k_s[kk], v_s[kk], ka, va)
+            else:  # attention and cache update of the scale in one launch (the event pair then covers both)
+                hk.heatkv_attend_append_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk],
+                                              att_ws[kk])
+                if i_timed is not None:
+                    ev[i_timed][kk][1].record()
 
     for _ in range(args.warmup):
         step()
@@ -192,7 +200,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: 1 layer x {H} heads x d{d} {cfg['dtype']}, batch {nb}, "
                                f"{K} scales ({c[-1]} tokens), {cfg['factor']}x budget, sinks {s}",
-                   "attend_only": bool(args.attend_only)},
+                   "attend_only": bool(args.attend_only), "fused_append": not args.separate_append},
         "attend_scale_tflops": round(att_tflops, 2),
         "attend_scale_ms_per_step": round(total_att_ms, 4),
         "attend_pct_of_bf16_peak": round(100 * att_tflops / PEAK_BF16_TFLOPS, 2),
@@ -274,8 +282,11 @@ def run_stack(args, dev):
             for l in range(L):
                 if i_timed is not None and l == 0:
                     ev[i_timed][kk][0].record()
-                hk.heatkv_attend_scale(plan, l, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk])
-                hk.heatkv_append_scale(plan, l, kk, k_s[kk], v_s[kk], ka, va)
+                if args.separate_append:
+                    hk.heatkv_attend_scale(plan, l, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk])
+                    hk.heatkv_append_scale(plan, l, kk, k_s[kk], v_s[kk], ka, va)
+                else:
+                    hk.heatkv_attend_append_scale(plan, l, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk])
             if i_timed is not None:
                 ev[i_timed][kk][1].record()
 

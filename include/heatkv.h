@@ -197,6 +197,16 @@ int heatkv_attend_scale(heatkv_plan* plan, int layer, int k, const void* q, cons
                         const void* v_cur, const void* k_arena, const void* v_arena, float sm_scale,
                         void* out, void* ws, size_t ws_bytes, void* stream);
 
+/* attend_scale(layer,k) and append_scale(layer,k) in one launch (Sec. 3.3: the cache update that follows a
+ * layer's attention).  Same arguments and results as the two calls made one after the other; the row copies of
+ * the cache update run as extra workgroups next to the attention workgroups, which saves one kernel's start
+ * and finish latency per layer and scale.  Legal because the update only writes the layer's next region, which
+ * the attention of this scale never reads.  k = K-1 is attention only.
+ */
+int heatkv_attend_append_scale(heatkv_plan* plan, int layer, int k, const void* q, const void* k_cur,
+                               const void* v_cur, void* k_arena, void* v_arena, float sm_scale, void* out,
+                               void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

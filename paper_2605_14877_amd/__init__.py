@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     calibrate,
     heatkv_accumulate_beta,
     heatkv_append_scale,
+    heatkv_attend_append_scale,
     heatkv_attend_scale,
     heatkv_build_schedule,
     heatkv_calibrate,

@@ -86,6 +86,8 @@ def lib():
     L.heatkv_attend_workspace_bytes.argtypes = [vp, C.c_int, C.c_int]
     L.heatkv_attend_scale.restype = C.c_int
     L.heatkv_attend_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.heatkv_attend_append_scale.restype = C.c_int
+    L.heatkv_attend_append_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
     _lib = L
     return L
 
@@ -242,3 +244,10 @@ def heatkv_attend_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, sm_sc
     _check(lib().heatkv_attend_scale(plan.handle, layer, k, _ptr(q), _ptr(k_cur), _ptr(v_cur), _ptr(k_arena),
                                      _ptr(v_arena), float(sm_scale), _ptr(out), _ptr(ws), ws_bytes,
                                      _stream() if stream is None else stream))
+
+
+def heatkv_attend_append_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, sm_scale, out, ws=None, stream=None):
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().heatkv_attend_append_scale(plan.handle, layer, k, _ptr(q), _ptr(k_cur), _ptr(v_cur), _ptr(k_arena),
+                                            _ptr(v_arena), float(sm_scale), _ptr(out), _ptr(ws), ws_bytes,
+                                            _stream() if stream is None else stream))

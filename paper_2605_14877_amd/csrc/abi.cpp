@@ -250,9 +250,12 @@ size_t heatkv_attend_workspace_bytes(const heatkv_plan* plan, int layer, int k) 
                                         plan->max_len[plan->idx(k, layer)]);
 }
 
-int heatkv_attend_scale(heatkv_plan* plan, int layer, int k, const void* q, const void* k_cur, const void* v_cur,
-                        const void* k_arena, const void* v_arena, float sm_scale, void* out, void* ws,
-                        size_t ws_bytes, void* stream) {
+namespace {
+
+// Shared body of heatkv_attend_scale and heatkv_attend_append_scale.
+int attend_impl(heatkv_plan* plan, int layer, int k, const void* q, const void* k_cur, const void* v_cur,
+                const void* k_arena, const void* v_arena, void* k_arena_rw, void* v_arena_rw, bool with_append,
+                float sm_scale, void* out, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_plan_index(plan, layer, k);
   if (rc) return rc;
   if (!q || !k_cur || !v_cur || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
@@ -262,6 +265,8 @@ int heatkv_attend_scale(heatkv_plan* plan, int layer, int k, const void* q, cons
   if (need > 0 && (!ws || ws_bytes < need)) return fail(HEATKV_EINVAL, "attend workspace too small");
   if (plan->dtype == HEATKV_BF16 && plan->d != 128)
     return fail(HEATKV_EINVAL, "bf16 attention supports head dimension 128 only");
+  const int ndesc = (with_append && k < plan->K - 1) ? plan->desc_count[plan->idx(k, layer)] : 0;
+  if (ndesc > 0 && (!k_arena_rw || !v_arena_rw)) return fail(HEATKV_EINVAL, "null arena pointer");
   if ((rc = ensure_uploaded(plan))) return rc;
   heatkv::AttendArgs a{};
   a.dtype = plan->dtype;
@@ -284,9 +289,32 @@ int heatkv_attend_scale(heatkv_plan* plan, int layer, int k, const void* q, cons
   a.sm_scale = sm_scale;
   a.ws = ws;
   a.ws_bytes = ws_bytes;
+  if (ndesc > 0) {
+    a.descs = plan->dev.descs + plan->desc_begin[plan->idx(k, layer)];
+    a.ndesc = ndesc;
+    a.row_bytes = int(plan->d * plan->elem_size());
+    a.k_arena_rw = k_arena_rw;
+    a.v_arena_rw = v_arena_rw;
+  }
   hipError_t e = heatkv::launch_attend(a, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "attend_scale launch");
   return HEATKV_OK;
+}
+
+}  // namespace
+
+int heatkv_attend_scale(heatkv_plan* plan, int layer, int k, const void* q, const void* k_cur, const void* v_cur,
+                        const void* k_arena, const void* v_arena, float sm_scale, void* out, void* ws,
+                        size_t ws_bytes, void* stream) {
+  return attend_impl(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, nullptr, nullptr, false, sm_scale, out, ws,
+                     ws_bytes, stream);
+}
+
+int heatkv_attend_append_scale(heatkv_plan* plan, int layer, int k, const void* q, const void* k_cur,
+                               const void* v_cur, void* k_arena, void* v_arena, float sm_scale, void* out, void* ws,
+                               size_t ws_bytes, void* stream) {
+  return attend_impl(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, k_arena, v_arena, true, sm_scale, out, ws,
+                     ws_bytes, stream);
 }
 
 size_t heatkv_calibrate_workspace_bytes(const heatkv_shape* shape, int k1) {

@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include "copy_rows.h"
 #include "device_util.h"
 #include "kernels.h"
 
@@ -26,6 +27,10 @@ struct AttendParams {
   void* out;
   float sm_scale;
   int n_qtiles;
+  // Workgroups with blockIdx.x >= attend_blocks run the fused cache update (copy descriptor, batch entry).
+  int attend_blocks;
+  int ndesc;
+  CopyParams copy;
 };
 
 // ---------------------------------------------------------------------------
@@ -65,6 +70,11 @@ __device__ __forceinline__ int swizzle_of_row(int row) { return ((row & 3) << 1)
 __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[2][2][TILE_BYTES];  // [buffer][K,V]
 
+  if (static_cast<int>(blockIdx.x) >= p.attend_blocks) {  // fused append: a plain row copy
+    const int j = blockIdx.x - p.attend_blocks;
+    copy_rows_block(p.copy, j % p.ndesc, j / p.ndesc);
+    return;
+  }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform, kept in a scalar register
   const int n = lane & 31, hl = lane >> 5;
@@ -337,6 +347,11 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(AttendParams p) {
   __shared__ float Vs[FN][D];
   __shared__ float Ps[FQ][FN];
 
+  if (static_cast<int>(blockIdx.x) >= p.attend_blocks) {  // fused append: a plain row copy
+    const int j = blockIdx.x - p.attend_blocks;
+    copy_rows_block(p.copy, j % p.ndesc, j / p.ndesc);
+    return;
+  }
   const int tid = threadIdx.x, r = tid >> 4, g = tid & 15;
   int id = blockIdx.x;
   const int qt = id % p.n_qtiles;
@@ -444,15 +459,32 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   p.v_arena = a.v_arena;
   p.out = a.out;
   p.sm_scale = a.sm_scale;
+  p.ndesc = a.ndesc;
+  unsigned copy_blocks = 0;
+  if (a.ndesc > 0) {
+    if (a.row_bytes % 16 != 0) return hipErrorInvalidValue;
+    p.copy.chunks_per_row = a.row_bytes / 16;
+    p.copy.H = a.H;
+    p.copy.t_k = a.t_k;
+    p.copy.arena_tokens = a.arena_tokens;
+    p.copy.descs = a.descs;
+    p.copy.k_new = static_cast<const uint4*>(a.k_cur);
+    p.copy.v_new = static_cast<const uint4*>(a.v_cur);
+    p.copy.k_arena = static_cast<uint4*>(a.k_arena_rw);
+    p.copy.v_arena = static_cast<uint4*>(a.v_arena_rw);
+    copy_blocks = unsigned(a.ndesc) * a.batch;
+  }
   if (a.dtype == HEATKV_BF16) {
     if (a.d != 128) return hipErrorInvalidValue;
     p.n_qtiles = (a.t_k + BM - 1) / BM;
     const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
-    const unsigned grid = unsigned(p.n_qtiles) * pairs8;
-    hipLaunchKernelGGL(attend_bf16_d128_kernel, dim3(grid), dim3(256), 0, stream, p);
+    p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
+    hipLaunchKernelGGL(attend_bf16_d128_kernel, dim3(unsigned(p.attend_blocks) + copy_blocks), dim3(256), 0, stream,
+                       p);
   } else {
     p.n_qtiles = (a.t_k + FQ - 1) / FQ;
-    const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
+    p.attend_blocks = int(unsigned(p.n_qtiles) * a.H * a.batch);
+    const unsigned grid = unsigned(p.attend_blocks) + copy_blocks;
     if (a.d == 64)
       hipLaunchKernelGGL(attend_f32_kernel<64>, dim3(grid), dim3(256), 0, stream, p);
     else if (a.d == 128)

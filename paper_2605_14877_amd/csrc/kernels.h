@@ -23,6 +23,12 @@ struct AttendArgs {
   float sm_scale;
   void* ws;
   size_t ws_bytes;
+  // Optional fused cache update (append_scale of the same layer and scale): extra workgroups of the same
+  // launch run these copy descriptors.  ndesc == 0: attention only.
+  const CopyDesc* descs = nullptr;
+  int ndesc = 0;
+  int row_bytes = 0;
+  void *k_arena_rw = nullptr, *v_arena_rw = nullptr;
 };
 
 size_t attend_workspace_bytes(int dtype, int d, int H, int batch, int t_k, int max_len);

@@ -9,7 +9,7 @@ import paper_2605_14877_amd as hk
 from oracle import heatkv_oracle as orc
 
 
-def device_generation(plan, layer, q, k, v, t0, sm_scale, append_first=False, arenas=None):
+def device_generation(plan, layer, q, k, v, t0, sm_scale, append_first=False, arenas=None, fused=False):
     """attend+append for scales 0..K-1 of one layer.  q,k,v: device [batch,H,c_K,d].  Returns list of outputs."""
     c = hi.cumulative_tokens(t0)
     dev = q.device
@@ -24,7 +24,9 @@ def device_generation(plan, layer, q, k, v, t0, sm_scale, append_first=False, ar
         out = torch.empty_like(qk)
         wsb = plan.attend_workspace_bytes(layer, kk)
         ws = torch.empty(max(wsb, 1), dtype=torch.uint8, device=dev)
-        if append_first:
+        if fused:
+            hk.heatkv_attend_append_scale(plan, layer, kk, qk, kc, vc, ka, va, sm_scale, out, ws)
+        elif append_first:
             # the arena region of scale kk must stay intact: appending first is only legal because
             # append writes the scale-(kk+1) region into free space
             hk.heatkv_append_scale(plan, layer, kk, kc, vc, ka, va)

@@ -83,8 +83,11 @@ def _run_stack(name, layers, n_calib_sets, seed, n_samples, rows_per_sample=24):
             q, k, v = data[l]
             qk, kc, vc = q[:, :, sl].contiguous(), k[:, :, sl].contiguous(), v[:, :, sl].contiguous()
             out = torch.empty_like(qk)
-            hk.heatkv_attend_scale(plan, l, kk, qk, kc, vc, ka, va, sm, out)
-            hk.heatkv_append_scale(plan, l, kk, kc, vc, ka, va)
+            if l % 2:  # alternate the fused launch and the two separate launches
+                hk.heatkv_attend_append_scale(plan, l, kk, qk, kc, vc, ka, va, sm, out)
+            else:
+                hk.heatkv_attend_scale(plan, l, kk, qk, kc, vc, ka, va, sm, out)
+                hk.heatkv_append_scale(plan, l, kk, kc, vc, ka, va)
             outs[(l, kk)] = out
     torch.cuda.synchronize()
 

@@ -59,6 +59,10 @@ def test_tiny_fp32_explicit_half_budget_schedule():
     outs2 = device_generation(plan, 0, *_dev(q, k, v), t0, sm, append_first=True)
     for a, b in zip(outs, outs2):
         assert torch.equal(a, b)
+    # neither does running both in one launch
+    outs3 = device_generation(plan, 0, *_dev(q, k, v), t0, sm, fused=True)
+    for a, b in zip(outs, outs3):
+        assert torch.equal(a, b)
 
 
 def test_tiny_fp32_full_budget_equals_uncompressed_attention():
@@ -118,7 +122,7 @@ def test_fp32_schedule_from_alg1_multi_layer(d, L, H, sides, s, den, batch):
         _check_all(outs[l], *qkv[l], t0, ref["present"], l, sm, TOL["f32"])
 
 
-def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None):
+def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None, fused=False):
     t0 = hi.tokens_per_scale(sides)
     c = hi.cumulative_tokens(t0)
     K = len(t0)
@@ -132,13 +136,22 @@ def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None):
     plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * d * 2, s)
     ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
     q, k, v = hi.make_qkv(seed, 0, cfg, w=w)
-    outs = device_generation(plan, 0, *_dev(q, k, v), t0, sm)
+    outs = device_generation(plan, 0, *_dev(q, k, v), t0, sm, fused=fused)
+    if fused:  # the fused launch must reproduce the two separate launches bit for bit
+        outs_sep = device_generation(plan, 0, *_dev(q, k, v), t0, sm)
+        for a, b in zip(outs, outs_sep):
+            assert torch.equal(a, b)
     return _check_all(outs, q, k, v, t0, ref["present"], 0, sm, TOL["bf16"], sample_from=sample_from)
 
 
 def test_bf16_small_ragged_scales():
     # several key tiles, ragged tails in both the query and the key direction
     _bf16_case(1, 4, (1, 2, 4, 6, 8, 11, 13), 3, 3, 2, seed=2)
+
+
+def test_bf16_fused_attend_append_medium():
+    # attend + append in one launch, scales up to 32x32 tokens, several key tiles per head
+    _bf16_case(1, 6, (1, 2, 4, 6, 8, 12, 16, 20, 24, 32), 3, 4, 2, seed=5, fused=True)
 
 
 def test_bf16_layer2b_full_size():
