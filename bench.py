@@ -106,8 +106,7 @@ def main():
     def calibrate_and_plan():
         beta.zero_()
         for k1 in range(K):
-            hk.heatkv_calibrate(shape, 0, k1, q_s[k1], kall_s[k1], sm, mass, cal_ws[k1])
-            hk.heatkv_accumulate_beta(shape, 0, k1, mass, 1.0 / nb, beta)
+            hk.heatkv_calibrate_accumulate(shape, 0, k1, q_s[k1], kall_s[k1], sm, 1.0 / nb, beta, mass, cal_ws[k1])
         beta_h = beta.cpu().numpy()
         plan = hk.heatkv_build_schedule(shape, beta_h, budget_bytes, s)
         plan.upload()

@@ -104,6 +104,13 @@ int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q
 int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const float* mass, float weight,
                            float* beta, void* stream);
 
+/* heatkv_calibrate followed by heatkv_accumulate_beta with one launch fewer (Sec. 3.1, Eq. 2 and the dataset
+ * average): same arithmetic in the same order, hence the same bits.  mass may be null when the per-row masses
+ * are not wanted. */
+int heatkv_calibrate_accumulate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
+                                float sm_scale, float weight, float* beta, float* mass, void* ws, size_t ws_bytes,
+                                void* stream);
+
 /* ---------------------------------------------------------------------------
  * Schedule construction (Sec. 3.1 Eq. 3-4, Sec. 3.2 Eq. 5, Sec. 3.3 Alg. 1, App. A Alg. 2).
  * Host only, integer arithmetic except for the fp64 sums that rank the heads.

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     heatkv_attend_scale,
     heatkv_build_schedule,
     heatkv_calibrate,
+    heatkv_calibrate_accumulate,
     heatkv_load_schedule,
     library_path,
 )

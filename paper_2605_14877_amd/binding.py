@@ -52,6 +52,9 @@ def lib():
     L.heatkv_calibrate_workspace_bytes.argtypes = [sp, C.c_int]
     L.heatkv_calibrate.restype = C.c_int
     L.heatkv_calibrate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.heatkv_calibrate_accumulate.restype = C.c_int
+    L.heatkv_calibrate_accumulate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, C.c_float, vp, vp, vp,
+                                              C.c_size_t, vp]
     L.heatkv_accumulate_beta.restype = C.c_int
     L.heatkv_accumulate_beta.argtypes = [sp, C.c_int, C.c_int, vp, C.c_float, vp, vp]
     L.heatkv_build_schedule.restype = C.c_int
@@ -251,3 +254,10 @@ def heatkv_attend_append_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena
     _check(lib().heatkv_attend_append_scale(plan.handle, layer, k, _ptr(q), _ptr(k_cur), _ptr(v_cur), _ptr(k_arena),
                                             _ptr(v_arena), float(sm_scale), _ptr(out), _ptr(ws), ws_bytes,
                                             _stream() if stream is None else stream))
+
+
+def heatkv_calibrate_accumulate(shape, layer, k1, q, k_all, sm_scale, weight, beta, mass, ws, stream=None):
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().heatkv_calibrate_accumulate(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale),
+                                             float(weight), _ptr(beta), _ptr(mass), _ptr(ws), ws_bytes,
+                                             _stream() if stream is None else stream))

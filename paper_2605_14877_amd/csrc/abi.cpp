@@ -323,13 +323,15 @@ size_t heatkv_calibrate_workspace_bytes(const heatkv_shape* shape, int k1) {
   return heatkv::calibrate_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K, shape->t[k1]);
 }
 
-int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all, float sm_scale,
-                     float* mass, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+
+int calibrate_impl(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all, float sm_scale,
+                   float* mass, float weight, float* beta, void* ws, size_t ws_bytes, void* stream) {
   int rc = heatkv::check_shape(shape);
   if (rc) return rc;
   if (layer < 0 || layer >= shape->L) return fail(HEATKV_EINVAL, "layer out of range");
   if (k1 < 0 || k1 >= shape->K) return fail(HEATKV_EINVAL, "scale index out of range");
-  if (!q || !k_all || !mass) return fail(HEATKV_EINVAL, "null tensor pointer");
+  if (!q || !k_all || (!mass && !beta)) return fail(HEATKV_EINVAL, "null tensor pointer");
   if (shape->dtype == HEATKV_BF16 && shape->d != 128)
     return fail(HEATKV_EINVAL, "bf16 calibration supports head dimension 128 only");
   const size_t need =
@@ -348,9 +350,27 @@ int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q
   a.sm_scale = sm_scale;
   a.mass = mass;
   a.ws = ws;
+  a.beta = beta;
+  a.weight = weight;
+  a.layer = layer;
   hipError_t e = heatkv::launch_calibrate(a, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "calibrate launch");
   return HEATKV_OK;
+}
+
+}  // namespace
+
+int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all, float sm_scale,
+                     float* mass, void* ws, size_t ws_bytes, void* stream) {
+  if (!mass) return fail(HEATKV_EINVAL, "null tensor pointer");
+  return calibrate_impl(shape, layer, k1, q, k_all, sm_scale, mass, 0.f, nullptr, ws, ws_bytes, stream);
+}
+
+int heatkv_calibrate_accumulate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
+                                float sm_scale, float weight, float* beta, float* mass, void* ws, size_t ws_bytes,
+                                void* stream) {
+  if (!beta) return fail(HEATKV_EINVAL, "null tensor pointer");
+  return calibrate_impl(shape, layer, k1, q, k_all, sm_scale, mass, weight, beta, ws, ws_bytes, stream);
 }
 
 int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const float* mass, float weight, float* beta,

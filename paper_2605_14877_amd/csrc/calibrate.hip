@@ -29,7 +29,10 @@ struct CalibParams {
   const void *q, *k_all;
   float sm_scale;
   float* partial;  // [batch*H][n_qtiles][K]
-  float* mass;     // [batch*H][K]
+  float* mass;     // [batch*H][K], may be null in the accumulating variant
+  float* beta;     // [L][H][K][K] or null
+  float weight;
+  int layer;
 };
 
 // ---------------------------------------------------------------------------
@@ -307,6 +310,26 @@ __global__ void calibrate_finish_kernel(CalibParams p) {
   p.mass[i] = v;
 }
 
+// Same reduction followed by the dataset average in one pass: one thread per (head, key block) walks the batch
+// rows in order, so the result has the bits of calibrate_finish_kernel followed by accumulate_beta_kernel.
+__global__ void calibrate_finish_accumulate_kernel(CalibParams p) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= p.H * p.K) return;
+  const int h = i / p.K, j = i % p.K;
+  float acc = 0.f;
+  for (int b = 0; b < p.batch; ++b) {
+    const long long bh = static_cast<long long>(b) * p.H + h;
+    float v = 0.f;
+    if (j <= p.k1) {
+      for (int qt = 0; qt < p.n_qtiles; ++qt) v += p.partial[(bh * p.n_qtiles + qt) * p.K + j];
+      v /= static_cast<float>(p.t_k1);
+    }
+    if (p.mass) p.mass[bh * p.K + j] = v;
+    acc += v;
+  }
+  p.beta[((static_cast<long long>(p.layer) * p.H + h) * p.K + p.k1) * p.K + j] += p.weight * acc;
+}
+
 __global__ void accumulate_beta_kernel(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
                                        float* beta) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -347,6 +370,9 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
   p.sm_scale = a.sm_scale;
   p.partial = static_cast<float*>(a.ws);
   p.mass = a.mass;
+  p.beta = a.beta;
+  p.weight = a.weight;
+  p.layer = a.layer;
   const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
   if (a.dtype == HEATKV_BF16) {
     if (a.d != 128) return hipErrorInvalidValue;
@@ -362,8 +388,12 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int total = a.batch * a.H * a.K;
-  hipLaunchKernelGGL(calibrate_finish_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, p);
+  if (a.beta) {
+    hipLaunchKernelGGL(calibrate_finish_accumulate_kernel, dim3((a.H * a.K + 255) / 256), dim3(256), 0, stream, p);
+  } else {
+    const int total = a.batch * a.H * a.K;
+    hipLaunchKernelGGL(calibrate_finish_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, p);
+  }
   return hipGetLastError();
 }
 

@@ -52,6 +52,10 @@ struct CalibrateArgs {
   float sm_scale;
   float* mass;
   void* ws;
+  // Optional fused dataset average: beta[layer][h][k1][:] += weight * sum_b mass[b][h][:] (mass may then be null).
+  float* beta = nullptr;
+  float weight = 0.f;
+  int layer = 0;
 };
 size_t calibrate_workspace_bytes(int dtype, int d, int H, int batch, int K, int t_k1);
 hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);

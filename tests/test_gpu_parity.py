@@ -189,3 +189,13 @@ def test_calibrate_tiny_fp32_and_bf16_small():
                     want = orc.beta_row(q[b, h].double().numpy(), k[b, h].double().numpy(), t1, k1 + 1, sm)[1:]
                     assert np.abs(got[b, h] - want).max() <= 1e-4, (dtype, k1, b, h)
             assert np.abs(got.sum(-1) - 1.0).max() <= 1e-4
+            # the accumulating variant gives the bits of calibrate followed by accumulate_beta
+            beta_a = torch.zeros(1, H, K, K, device="cuda")
+            beta_b = torch.zeros(1, H, K, K, device="cuda")
+            hk.heatkv_accumulate_beta(shape, 0, k1, mass, 0.5, beta_a)
+            mass3 = torch.empty_like(mass)
+            hk.heatkv_calibrate_accumulate(shape, 0, k1, qk, ka, sm, 0.5, beta_b, mass3, ws)
+            assert torch.equal(beta_a, beta_b) and torch.equal(mass, mass3)
+            beta_c = torch.zeros(1, H, K, K, device="cuda")
+            hk.heatkv_calibrate_accumulate(shape, 0, k1, qk, ka, sm, 0.5, beta_c, None, ws)
+            assert torch.equal(beta_a, beta_c)
