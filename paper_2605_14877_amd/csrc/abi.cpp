@@ -3,6 +3,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include <hip/hip_runtime_api.h>
 
@@ -22,25 +23,12 @@ int hip_fail(hipError_t e, const char* what) {
   return fail(HEATKV_EHIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-template <typename T>
-int upload_vec(const std::vector<T>& v, T** dst) {
-  *dst = nullptr;
-  if (v.empty()) return HEATKV_OK;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(dst), v.size() * sizeof(T));
-  if (e != hipSuccess) return fail(HEATKV_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
-  e = hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
-  if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
-  return HEATKV_OK;
-}
-
 void free_device(heatkv::DeviceTables& d) {
-  if (d.run_row) (void)hipFree(d.run_row);
-  if (d.run_len) (void)hipFree(d.run_len);
-  if (d.head_order) (void)hipFree(d.head_order);
-  if (d.descs) (void)hipFree(d.descs);
+  if (d.block) (void)hipFree(d.block);
   d = heatkv::DeviceTables{};
 }
 
+// One device allocation and one copy for all plan tables (16-byte aligned sections).
 int ensure_uploaded(heatkv_plan* p) {
   std::lock_guard<std::mutex> lock(p->upload_mutex);
   int dev = -1;
@@ -48,11 +36,30 @@ int ensure_uploaded(heatkv_plan* p) {
   if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
   if (p->dev.device == dev) return HEATKV_OK;
   if (p->dev.device >= 0) return fail(HEATKV_EINVAL, "plan was uploaded to another device");
-  int rc;
-  if ((rc = upload_vec(p->run_row, &p->dev.run_row))) return rc;
-  if ((rc = upload_vec(p->run_len, &p->dev.run_len))) return rc;
-  if ((rc = upload_vec(p->head_order, &p->dev.head_order))) return rc;
-  if ((rc = upload_vec(p->descs, &p->dev.descs))) return rc;
+  auto pad = [](size_t n) { return (n + 15) / 16 * 16; };
+  const size_t n3 = p->run_row.size() * sizeof(int32_t);
+  const size_t nd = p->descs.size() * sizeof(heatkv::CopyDesc);
+  const size_t o_row = 0, o_len = o_row + pad(n3), o_ord = o_len + pad(n3), o_desc = o_ord + pad(n3);
+  const size_t total = o_desc + pad(nd) + 16;
+  std::vector<unsigned char> host(total, 0);
+  std::memcpy(host.data() + o_row, p->run_row.data(), n3);
+  std::memcpy(host.data() + o_len, p->run_len.data(), n3);
+  std::memcpy(host.data() + o_ord, p->head_order.data(), n3);
+  if (nd) std::memcpy(host.data() + o_desc, p->descs.data(), nd);
+  void* block = nullptr;
+  e = hipMalloc(&block, total);
+  if (e != hipSuccess) return fail(HEATKV_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
+  e = hipMemcpy(block, host.data(), total, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(block);
+    return hip_fail(e, "hipMemcpy");
+  }
+  unsigned char* base = static_cast<unsigned char*>(block);
+  p->dev.block = block;
+  p->dev.run_row = reinterpret_cast<int32_t*>(base + o_row);
+  p->dev.run_len = reinterpret_cast<int32_t*>(base + o_len);
+  p->dev.head_order = reinterpret_cast<int32_t*>(base + o_ord);
+  p->dev.descs = reinterpret_cast<heatkv::CopyDesc*>(base + o_desc);
   p->dev.device = dev;
   return HEATKV_OK;
 }

@@ -23,6 +23,7 @@ struct CopyDesc {
 
 struct DeviceTables {
   int device = -1;
+  void* block = nullptr;          // one allocation holding the four tables below
   int32_t* run_row = nullptr;     // [K][L][H] first arena row of the head's run
   int32_t* run_len = nullptr;     // [K][L][H] retained prior tokens
   int32_t* head_order = nullptr;  // [K][L][H] heads by descending run length
