@@ -28,6 +28,9 @@ struct AttendParams {
   float sm_scale;
   int n_qtiles;
   // Workgroups with blockIdx.x >= attend_blocks run the fused cache update (copy descriptor, batch entry).
+  // They sit at the end of the grid on purpose: there they fill the slots that the last attention workgroups
+  // leave one by one.  Spread through the grid instead, their memory traffic lengthened the latency of the
+  // attention workgroups' tile fetches and the launch became up to 1.4x slower.
   int attend_blocks;
   int ndesc;
   CopyParams copy;
@@ -279,12 +282,16 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   };
 
   f32x16 s_cur[2], s_nxt[2];
+  // A wavefront whose 32 query rows all lie past t_k (ragged last query tile) keeps loading its share of
+  // every tile and keeps the barriers, but leaves the matrix cores to the other workgroup on the unit.
+  const bool active = qt * BM + wave * 32 < t_k;
   // Steady-state step for tile `it` (it + 1 < tiles_all); K(it+1) sits in K buffer kb1, V(it) in V buffer vb0.
   auto pipe_step = [&](int it, auto kb1, auto vb0) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (it + 2 < tiles_all) issue_k(it + 2, decltype(vb0)::value);      // K buffer it & 1 was read by step it-1
     issue_v(it + 1, decltype(kb1)::value);                              // V buffer (it+1) & 1 likewise
+    if (!active) return;
     scores(s_nxt, kb1);
     accumulate(s_cur, vb0);
     settle(it + 1, s_nxt);
@@ -292,14 +299,23 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
     for (int cb = 0; cb < 2; ++cb) s_cur[cb] = s_nxt[cb];
   };
 
-  // Prologue: K(0) alone, then its scores; K(1) and V(0) go out before the loop.
+  // Prologue: K(0), K(1) and V(0) all go out at once (one memory round trip instead of two before the loop,
+  // which is what the short scales are made of); loads return in issue order, so waiting until at most the
+  // eight younger copies are outstanding means K(0) has landed.
   issue_k(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (tiles_all > 1) {
+    issue_k(1, 1);
+    issue_v(0, 0);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  } else {
+    issue_v(0, 0);
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  }
   __syncthreads();
-  scores(s_cur, std::integral_constant<int, 0>{});
-  settle(0, s_cur);
-  if (tiles_all > 1) issue_k(1, 1);
-  issue_v(0, 0);
+  if (active) {
+    scores(s_cur, std::integral_constant<int, 0>{});
+    settle(0, s_cur);
+  }
   int it = 0;
   for (; it + 2 < tiles_all; it += 2) {
     pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
@@ -312,6 +328,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Epilogue: the last tile has scores but no successor.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  if (!active) return;
   if (it & 1)
     accumulate(s_cur, std::integral_constant<int, 1>{});
   else
@@ -484,11 +501,11 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   } else {
     p.n_qtiles = (a.t_k + FQ - 1) / FQ;
     p.attend_blocks = int(unsigned(p.n_qtiles) * a.H * a.batch);
-    const unsigned grid = unsigned(p.attend_blocks) + copy_blocks;
+    const dim3 grid(unsigned(p.attend_blocks) + copy_blocks);
     if (a.d == 64)
-      hipLaunchKernelGGL(attend_f32_kernel<64>, dim3(grid), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL(attend_f32_kernel<64>, grid, dim3(256), 0, stream, p);
     else if (a.d == 128)
-      hipLaunchKernelGGL(attend_f32_kernel<128>, dim3(grid), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL(attend_f32_kernel<128>, grid, dim3(256), 0, stream, p);
     else
       return hipErrorInvalidValue;
   }

@@ -36,24 +36,25 @@ __device__ __forceinline__ void copy_rows_block(const CopyParams& p, int desc, i
   uint4* kd = p.k_arena + dst0;
   uint4* vd = p.v_arena + dst0;
   const int total = d.nrows * p.chunks_per_row;
-  for (int i = threadIdx.x; i < total; i += 4 * 256) {
-    uint4 kk[4], vv[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = i + u * 256;
-      if (j < total) {
-        kk[u] = ks[j];
-        vv[u] = vs[j];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = i + u * 256;
-      if (j < total) {
-        kd[j] = kk[u];
-        vd[j] = vv[u];
-      }
-    }
+  // Whole groups of 4 x 256 chunks take the unconditional path (eight loads in flight per lane, all values
+  // in registers); the remainder goes one chunk per lane at a time.
+  const int whole = total & ~1023;
+  for (int i = threadIdx.x; i < whole; i += 4 * 256) {
+    const uint4 k0 = ks[i], k1 = ks[i + 256], k2 = ks[i + 512], k3 = ks[i + 768];
+    const uint4 v0 = vs[i], v1 = vs[i + 256], v2 = vs[i + 512], v3 = vs[i + 768];
+    kd[i] = k0;
+    kd[i + 256] = k1;
+    kd[i + 512] = k2;
+    kd[i + 768] = k3;
+    vd[i] = v0;
+    vd[i + 256] = v1;
+    vd[i + 512] = v2;
+    vd[i + 768] = v3;
+  }
+  for (int i = whole + threadIdx.x; i < total; i += 256) {
+    const uint4 k0 = ks[i], v0 = vs[i];
+    kd[i] = k0;
+    vd[i] = v0;
   }
 }
 
