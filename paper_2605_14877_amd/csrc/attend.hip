@@ -49,8 +49,8 @@ struct AttendParams {
 // store instructions), double-buffered with one barrier per tile.  A tile is
 // stored row-major, 256 bytes per row, unpadded; the 16-byte chunks of a row are
 // XOR-swizzled with the row number (the lane that fills an LDS slot simply
-// fetches the matching global chunk) so that both read patterns below are free of
-// bank conflicts.
+// fetches the matching global chunk), K tiles and V tiles each with the pattern
+// that keeps their read instruction free of bank conflicts.
 //
 // Scores are produced transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: K
 // rows are the A operand straight from LDS, Q stays in registers as the B operand.
@@ -66,9 +66,16 @@ constexpr int D128 = 128;
 constexpr int ROW_BYTES = 256;       // one bf16 row
 constexpr int TILE_BYTES = BN * ROW_BYTES;
 
-// Chunk swizzle: 8 consecutive rows map to 8 distinct values (16-byte row reads of the K operand), and 4
-// consecutive rows starting at a multiple of 4 map to values two apart (32-byte accesses of the V read).
-__device__ __forceinline__ int swizzle_of_row(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// Chunk swizzles.  The LDS has 64 four-byte banks (256 bytes per clock).
+// K tiles: ds_read_b128 serves 16 consecutive lanes per clock; they read the same logical chunk of 16
+// consecutive rows, so the chunk is XORed with row % 16 and the 16 accesses cover all 64 banks (measured
+// 246 bytes/clock per compute unit against 128 with an 8-row pattern).
+// V tiles: the transposing 8-byte read serves 32 lanes per clock, a block of 4 rows x 64 bytes; XORing the
+// 64-byte window index (chunk bits 2-3) with row % 4 puts the four rows on four different bank quarters
+// (measured 156-162 bytes/clock, the instruction's ceiling, against 125).
+// Both depend only on row % 16, so they are the same for the four rows a lane loads in one tile (16 apart).
+__device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
+__device__ __forceinline__ int swizzle_v(int row) { return (row & 3) << 2; }
 
 __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[2][2][TILE_BYTES];  // [buffer][K,V]
@@ -117,13 +124,12 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   const int tiles_all = tiles_cur + (n_prior + BN - 1) / BN;
 
   // Loader: wavefront w fills LDS bytes [(4j + w) KB, +1 KB) of a tile with instruction j = 0..3, lane L
-  // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16, slot L % 16.
-  int ld_off[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 4 * (4 * j + wave) + (lane >> 4);
-    ld_off[j] = row * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
-  }
+  // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16 = ld_row0 + 16 j, slot L % 16.  The
+  // swizzle is the same for all j, so one per-lane offset serves the four instructions (the 4 KB step
+  // between them goes into the scalar base address).
+  const int ld_row0 = 4 * wave + (lane >> 4);
+  const int ld_off_k = ld_row0 * ROW_BYTES + (((lane & 15) ^ swizzle_k(ld_row0)) << 4);
+  const int ld_off_v = ld_row0 * ROW_BYTES + (((lane & 15) ^ swizzle_v(ld_row0)) << 4);
   // The copy HBM -> LDS is issued as raw global_load_lds instructions (issue_k / issue_v below): the
   // compiler then does not see an LDS store it would have to order against the tile reads of the other
   // buffer (it would wait for the whole prefetch in the middle of the math).  Ordering is explicit
@@ -133,7 +139,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Reader offsets inside a tile.
   int k_off[8];  // K operand: row n (+32 cb), chunk 2 ks + hl
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * ROW_BYTES + (((2 * ks + hl) ^ swizzle_of_row(n)) << 4);
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * ROW_BYTES + (((2 * ks + hl) ^ swizzle_k(n)) << 4);
   // V operand through the transposing read: lane i of a 16-lane group points at row key0 + 4 hl + i / 4,
   // columns 32 dblk + 16 (group & 1) + 4 (i % 4) .. +3, and receives column i of that 4 x 16 block.
   const int tr_i = lane & 15, tr_grp = lane >> 4;
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
 #pragma unroll
   for (int dblk = 0; dblk < 4; ++dblk) {
     const int chunk = 4 * dblk + 2 * (tr_grp & 1) + ((tr_i & 3) >> 1);
-    v_off[dblk] = v_row * ROW_BYTES + ((chunk ^ swizzle_of_row(v_row)) << 4) + ((tr_i & 1) << 3);
+    v_off[dblk] = v_row * ROW_BYTES + ((chunk ^ swizzle_v(v_row)) << 4) + ((tr_i & 1) << 3);
   }
 
   f32x16 o[4];
@@ -171,14 +177,16 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
     const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int off = ld_off[j];
-      if (left < BN) {
-        const int row = 4 * (4 * j + wave) + (lane >> 4);
+      int off = ld_off_k;
+      const char* src = kb + j * (16 * ROW_BYTES);
+      if (left < BN) {  // ragged tile: rows past the end re-read the last valid row
+        const int row = ld_row0 + 16 * j;
         const int rr = row < left ? row : left - 1;
-        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_k(row)) << 4);
+        src = kb;
       }
       const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(kb) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(src) : "memory");
     }
   };
   auto issue_v = [&](int it, int buf) {
@@ -188,14 +196,16 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int off = ld_off[j];
+      int off = ld_off_v;
+      const char* src = vb + j * (16 * ROW_BYTES);
       if (left < BN) {
-        const int row = 4 * (4 * j + wave) + (lane >> 4);
+        const int row = ld_row0 + 16 * j;
         const int rr = row < left ? row : left - 1;
-        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_v(row)) << 4);
+        src = vb;
       }
       const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd), "v"(off), "s"(vb) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd), "v"(off), "s"(src) : "memory");
     }
   };
 

@@ -46,7 +46,9 @@ constexpr int CD = 128;
 constexpr int CROW_BYTES = 256;
 constexpr int CTILE_BYTES = CBN * CROW_BYTES;
 
-__device__ __forceinline__ int swizzle_of_row(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// Chunk swizzle of a K tile: ds_read_b128 serves 16 consecutive lanes per clock, which read one logical chunk
+// of 16 consecutive rows; XORing the chunk with row % 16 spreads them over all 64 LDS banks.
+__device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
 
 // Dynamic LDS: two K tiles, then blk_sum[k1+1][128], blk_max[k1+1][128], fin_max[128] (floats).
 __host__ __device__ constexpr size_t calib_lds_bytes(int k1) {
@@ -84,12 +86,10 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
   const float c = p.sm_scale * kLog2e;
 
   // HBM -> LDS copy of one tile (see the attention kernel: raw global_load_lds, explicit ordering).
-  int ld_off[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = 4 * (4 * j + wave) + (lane >> 4);
-    ld_off[j] = row * CROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
-  }
+  // Instruction j of wavefront w fills rows ld_row0 + 16 j; the swizzle depends on row % 16 only, so one
+  // per-lane offset serves all four (the 4 KB step goes into the scalar base address).
+  const int ld_row0 = 4 * wave + (lane >> 4);
+  const int ld_off = ld_row0 * CROW_BYTES + (((lane & 15) ^ swizzle_k(ld_row0)) << 4);
   const unsigned lds_base =
       static_cast<unsigned>(reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0])));
   auto issue_tile = [&](int k2, int tile, int buf) {
@@ -97,19 +97,21 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
     const char* kb = kbase + static_cast<long long>(p.c[k2] - p.t[k2] + tile * CBN) * CROW_BYTES;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int off = ld_off[j];
-      if (left < CBN) {
-        const int row = 4 * (4 * j + wave) + (lane >> 4);
+      int off = ld_off;
+      const char* src = kb + j * (16 * CROW_BYTES);
+      if (left < CBN) {  // ragged tile: rows past the end re-read the last valid row
+        const int row = ld_row0 + 16 * j;
         const int rr = row < left ? row : left - 1;
-        off = rr * CROW_BYTES + (((lane & 15) ^ swizzle_of_row(row)) << 4);
+        off = rr * CROW_BYTES + (((lane & 15) ^ swizzle_k(row)) << 4);
+        src = kb;
       }
       const unsigned kd = lds_base + buf * CTILE_BYTES + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(kb) : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(src) : "memory");
     }
   };
   int k_off[8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * CROW_BYTES + (((2 * ks + hl) ^ swizzle_of_row(n)) << 4);
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * CROW_BYTES + (((2 * ks + hl) ^ swizzle_k(n)) << 4);
 
   float m_run = -INFINITY, cur = 0.f;
   int k2 = 0, tile = 0;  // the tile being computed
