@@ -199,3 +199,35 @@ def test_calibrate_tiny_fp32_and_bf16_small():
             beta_c = torch.zeros(1, H, K, K, device="cuda")
             hk.heatkv_calibrate_accumulate(shape, 0, k1, qk, ka, sm, 0.5, beta_c, None, ws)
             assert torch.equal(beta_a, beta_c)
+
+
+def test_bf16_rising_logits_exercise_lazy_rescale():
+    # Keys are laid out so that, in the order the kernel walks them (current scale first, then the retained
+    # run), the row maxima keep rising: slowly inside a scale (many tiles below the rescaling threshold, a few
+    # crossings) and by a large jump at the change of segment.  Head 1 sees the mirror image (falling logits).
+    sides = (1, 2, 4, 8, 16, 24)
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K, H, d, batch = len(t0), 2, 128, 1
+    sm = 1.0 / np.sqrt(d)
+    g = torch.Generator().manual_seed(17)
+    q = (0.1 * torch.randn(batch, H, c[-1], d, generator=g))
+    k = (0.1 * torch.randn(batch, H, c[-1], d, generator=g))
+    v = torch.randn(batch, H, c[-1], d, generator=g)
+    for i in range(K):
+        lo = c[i] - t0[i]
+        ramp = torch.linspace(0.0, 21.0, t0[i]) + 30.0 * (K - 1 - i)   # earlier scales sit higher
+        k[:, :, lo:c[i], 0] = ramp
+    q[:, 0, :, 0] = 16.0
+    q[:, 1, :, 0] = -16.0
+    q, k, v = (x.to(torch.bfloat16) for x in (q, k, v))
+    present = np.zeros((K, 1, H, K), dtype=np.uint8)
+    for kk in range(K):
+        present[kk, 0, :, :kk] = 1
+    shape = hk.Shape(1, H, d, t0, batch, "bf16")
+    plan = hk.heatkv_load_schedule(shape, present)
+    outs = device_generation(plan, 0, *_dev(q, k, v), t0, sm)
+    worst = _check_all(outs, q, k, v, t0, present, 0, sm, TOL["bf16"])
+    for o in outs:
+        assert torch.isfinite(o.float()).all()
+    print("rising logits worst abs err", worst)
