@@ -50,6 +50,9 @@ def main():
                     help="call heatkv_attend_scale and heatkv_append_scale separately instead of the fused entry point")
     ap.add_argument("--graph", action="store_true",
                     help="stack workloads only: capture one generation pass in a HIP graph and time its replays")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the matrix-core probe (back-to-back bf16 MFMAs on zero and on random operands, "
+                         "run after the timed region and reported next to the roofline)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="profiling aid: after the timed region run one plain device copy of this many MiB "
                          "(a kernel of known HBM traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -226,6 +229,8 @@ def main():
         },
     }
 
+    if not args.no_mfma_probe:
+        result["roofline"]["mfma_probe"] = mfma_probe(dev)
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -235,6 +240,39 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(q, k, v, t0, plan, sm, d)
     print(json.dumps(result))
+
+
+def mfma_probe(dev):
+    """What the matrix cores of this GPU sustain on back-to-back independent bf16 MFMAs (no memory traffic, no
+    vector ALU work), for all-zero operands and for random operand bits.  The clock is power-limited, so the
+    second figure, not the datasheet peak, is what a kernel working on real data can approach."""
+    import torch
+
+    import paper_2605_14877_amd as hk
+
+    nbytes = hk.heatkv_probe_mfma_operand_bytes()
+    workgroups, iters = 2048, 2000
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device=dev)
+    flop = workgroups * 4 * iters * 32 * 32768.0
+    res = {"unit": "TFLOP/s", "instruction": "v_mfma_f32_32x32x16_bf16", "workgroups": workgroups, "iters": iters}
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    for name in ("zero_operands", "random_operands"):
+        if name == "zero_operands":
+            ops = torch.zeros(nbytes // 2, dtype=torch.bfloat16, device=dev)
+        else:
+            ops = torch.randn(nbytes // 2, device=dev, generator=g).to(torch.bfloat16)
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            hk.heatkv_probe_mfma(ops, out, workgroups, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        res[name] = round(flop / best / 1e9, 1)
+    return res
 
 
 def run_stack(args, dev):
@@ -332,6 +370,8 @@ def run_stack(args, dev):
                      "achieved": round(float(value), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(float(value) / PEAK_BF16_TFLOPS, 4), "traffic": None},
     }
+    if not args.no_mfma_probe:
+        result["roofline"]["mfma_probe"] = mfma_probe(dev)
     print(json.dumps(result))
 
 

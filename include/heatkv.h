@@ -214,6 +214,19 @@ int heatkv_attend_append_scale(heatkv_plan* plan, int layer, int k, const void* 
                                const void* v_cur, void* k_arena, void* v_arena, float sm_scale, void* out,
                                void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Measurement aid, not a step of the method: the bf16 matrix-core rate this GPU sustains for the caller's
+ * operand bits.  Every wavefront of `workgroups` x 256 threads issues iters x 32 independent
+ * v_mfma_f32_32x32x16_bf16 instructions (32768 FLOP each) on operands read once from `operands`, a device
+ * buffer of heatkv_probe_mfma_operand_bytes() bytes of bf16 values chosen by the caller (zeros, constants,
+ * random bits: the sustained clock depends on them); `out` is a device buffer of workgroups x 256 floats
+ * that receives the accumulators' sums (so that nothing is optimised away).  Asynchronous on `stream`; the
+ * caller times it.  FLOP = workgroups * 4 * iters * 32 * 32768.  Returns HEATKV_EINVAL for null pointers
+ * or non-positive sizes, HEATKV_EHIP if the launch fails.
+ */
+size_t heatkv_probe_mfma_operand_bytes(void);
+int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

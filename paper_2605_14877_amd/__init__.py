@@ -22,5 +22,7 @@ from .binding import (  # noqa: F401
     heatkv_calibrate,
     heatkv_calibrate_accumulate,
     heatkv_load_schedule,
+    heatkv_probe_mfma,
+    heatkv_probe_mfma_operand_bytes,
     library_path,
 )

@@ -91,6 +91,10 @@ def lib():
     L.heatkv_attend_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
     L.heatkv_attend_append_scale.restype = C.c_int
     L.heatkv_attend_append_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.heatkv_probe_mfma_operand_bytes.restype = C.c_size_t
+    L.heatkv_probe_mfma_operand_bytes.argtypes = []
+    L.heatkv_probe_mfma.restype = C.c_int
+    L.heatkv_probe_mfma.argtypes = [vp, vp, C.c_int, C.c_int, vp]
     _lib = L
     return L
 
@@ -261,3 +265,13 @@ def heatkv_calibrate_accumulate(shape, layer, k1, q, k_all, sm_scale, weight, be
     _check(lib().heatkv_calibrate_accumulate(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale),
                                              float(weight), _ptr(beta), _ptr(mass), _ptr(ws), ws_bytes,
                                              _stream() if stream is None else stream))
+
+
+def heatkv_probe_mfma_operand_bytes():
+    return int(lib().heatkv_probe_mfma_operand_bytes())
+
+
+def heatkv_probe_mfma(operands, out, workgroups, iters, stream=None):
+    """Measurement aid: back-to-back bf16 MFMAs on the caller's operand bits (see include/heatkv.h)."""
+    _check(lib().heatkv_probe_mfma(_ptr(operands), _ptr(out), int(workgroups), int(iters),
+                                   _stream() if stream is None else stream))

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheatkv.so")
-SOURCES = ["plan.cpp", "abi.cpp", "attend.hip", "append.hip", "calibrate.hip"]
+SOURCES = ["plan.cpp", "abi.cpp", "attend.hip", "append.hip", "calibrate.hip", "probe.hip"]
 
 # Packed-fp32 VALU forms are switched off for every device translation unit.
 HIP_FLAGS = [

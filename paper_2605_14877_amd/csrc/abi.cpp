@@ -393,4 +393,14 @@ int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const f
   return HEATKV_OK;
 }
 
+size_t heatkv_probe_mfma_operand_bytes(void) { return heatkv::probe_mfma_operand_bytes(); }
+
+int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iters, void* stream) {
+  if (!operands || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
+  if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20)) return fail(HEATKV_EINVAL, "probe size out of range");
+  hipError_t e = heatkv::launch_probe_mfma(operands, out, workgroups, iters, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "probe_mfma launch");
+  return HEATKV_OK;
+}
+
 }  // extern "C"

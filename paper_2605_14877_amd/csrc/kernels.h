@@ -63,4 +63,9 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);
 hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
                                   float* beta, hipStream_t stream);
 
+// Matrix-core probe: `workgroups` x 4 wavefronts each issue iters x 32 independent 32x32x16 bf16 MFMAs on
+// operands taken from `operands` (probe_mfma_operand_bytes() bytes); out receives workgroups x 256 floats.
+size_t probe_mfma_operand_bytes();
+hipError_t launch_probe_mfma(const void* operands, float* out, int workgroups, int iters, hipStream_t stream);
+
 }  // namespace heatkv

@@ -196,6 +196,10 @@ def test_error_codes():
     with pytest.raises(hk.HeatKVError) as e:
         hk.heatkv_append_scale(plan, 0, 1, None, None, None, None, stream=0)
     assert e.value.code == -1
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_probe_mfma(None, None, 1, 1, stream=0)
+    assert e.value.code == -1
+    assert hk.heatkv_probe_mfma_operand_bytes() == 65536
 
 
 def test_full_budget_plan_keeps_everything():

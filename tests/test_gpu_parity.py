@@ -231,3 +231,21 @@ def test_bf16_rising_logits_exercise_lazy_rescale():
     for o in outs:
         assert torch.isfinite(o.float()).all()
     print("rising logits worst abs err", worst)
+
+
+def test_mfma_probe_runs_and_is_deterministic():
+    # measurement aid: same operands, same sums; zero operands give zeros
+    n = hk.heatkv_probe_mfma_operand_bytes() // 2
+    g = torch.Generator(device="cuda").manual_seed(3)
+    ops = torch.randn(n, device="cuda", generator=g).to(torch.bfloat16)
+    out1 = torch.empty(4 * 256, device="cuda")
+    out2 = torch.empty(4 * 256, device="cuda")
+    hk.heatkv_probe_mfma(ops, out1, 4, 3)
+    hk.heatkv_probe_mfma(ops, out2, 4, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2) and torch.isfinite(out1).all() and out1.abs().max() > 0
+    hk.heatkv_probe_mfma(torch.zeros_like(ops), out1, 4, 3)
+    torch.cuda.synchronize()
+    assert (out1 == 0).all()
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_probe_mfma(ops, out1, 0, 3)
