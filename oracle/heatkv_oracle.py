@@ -16,12 +16,16 @@ Q = 0 closed forms, permutation and shift invariance; masses against row sums
 and the Q = 0 closed form; Eq. 5 against exact rational arithmetic and the
 total-cache identity; Alg. 1 against a hand-worked example
 (tests/golden/alg1_hand_example.txt), the budget/containment invariants, and,
-for the binary variant, brute-force minimum cardinality (Prop. 1).
+for the binary variant, brute-force minimum cardinality (Prop. 1); the rank
+dispersion of App. C against closed forms (identical runs, reversed orders)
+and against numpy's argsort/std on random tables.
 Parity unpinned: minimum cardinality of E_k in the scale-dependent variant
 (the paper proves it for the binary case only); there only the algorithm's
 steps are followed.
 """
 from __future__ import annotations
+
+import math
 
 import numpy as np
 
@@ -193,6 +197,39 @@ def cas_order(beta, L, H, K, s):
             scored.append((cas_sum(beta[l, h], K, s), l, h))
     scored.sort(key=lambda x: x[0])
     return [(l, h) for _, l, h in scored]
+
+
+def rank_dispersion(betas, L, H, K, s, binary=False):
+    """Stability of the head rankings over calibration runs (App. C, S-CAS stability).
+
+    betas: list of R tables, each [L+1, H+1, K+1, K+1] (1-based), one per calibration run.  For every source
+    scale i (s < i < K) each run's order O_i gives every head a rank position (0 = pruned first).  Per head:
+    the standard deviation of its R positions around the head's own mean position (population form, divide
+    by R: the appendix does not say which); the result for scale i is the mean of these over all heads.
+    Returns dict i -> float.  With `binary` the single CAS order is used for every i.
+    """
+    R = len(betas)
+    T = L * H
+    out = {}
+    per_run_binary = [cas_order(b, L, H, K, s) for b in betas] if binary else None
+    per_run = None if binary else [head_orders(b, L, H, K, s) for b in betas]
+    for i in range(s + 1, K):
+        pos = {}
+        for r in range(R):
+            order = per_run_binary[r] if binary else per_run[r][i]
+            for rank, lh in enumerate(order):
+                pos.setdefault(lh, []).append(rank)
+        total = 0.0
+        for l in range(1, L + 1):
+            for h in range(1, H + 1):
+                ranks = pos[(l, h)]
+                mean = sum(ranks) / R
+                var = 0.0
+                for x in ranks:
+                    var += (x - mean) * (x - mean)
+                total += math.sqrt(var / R)
+        out[i] = total / T
+    return out
 
 
 # --------------------------------------------------------------------------

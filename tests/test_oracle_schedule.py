@@ -257,3 +257,61 @@ def test_zero_based_present_view_matches_retained_scales():
     # once dropped a prior scale never returns
     for k in range(1, K - 1):
         assert np.all(pres[k + 1, :, :, :k] <= pres[k, :, :, :k])
+
+
+def _beta_with_scores(L, H, K, i_scores):
+    """A 1-based beta table whose S-CAS sum for source scale i of flat head j is i_scores[i][j]
+    (all of it placed in row tau = i + 1)."""
+    beta = np.zeros((L + 1, H + 1, K + 1, K + 1))
+    for i, sc in i_scores.items():
+        for j, v in enumerate(sc):
+            beta[j // H + 1, j % H + 1, i + 1, i] = v
+    return beta
+
+
+def test_rank_dispersion_closed_forms():
+    # App. C: identical runs give zero; two runs with exactly reversed orders put head at ranks r and T-1-r,
+    # so its deviation is |r - (T-1)/2| and the mean over heads is T/4 for even T.
+    L, H, K, s = 2, 3, 5, 1
+    T = L * H
+    up = {i: [float(j) for j in range(T)] for i in range(s + 1, K)}
+    down = {i: [float(T - j) for j in range(T)] for i in range(s + 1, K)}
+    a, b = _beta_with_scores(L, H, K, up), _beta_with_scores(L, H, K, down)
+    same = orc.rank_dispersion([a, a, a], L, H, K, s)
+    assert all(v == 0.0 for v in same.values()) and sorted(same) == list(range(s + 1, K))
+    rev = orc.rank_dispersion([a, b], L, H, K, s)
+    for i in range(s + 1, K):
+        assert abs(rev[i] - T / 4) < 1e-12
+    # one head swaps places with its neighbour in one of three runs: two heads have ranks (r, r, r+1) and
+    # (r+1, r+1, r): population std sqrt(2)/3 each, all others 0
+    sw = {i: list(up[i]) for i in up}
+    sw[2][0], sw[2][1] = up[2][1], up[2][0]
+    c = _beta_with_scores(L, H, K, sw)
+    one = orc.rank_dispersion([a, a, c], L, H, K, s)
+    assert abs(one[2] - 2 * (np.sqrt(2) / 3) / T) < 1e-12 and one[3] == 0.0
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_rank_dispersion_against_numpy_argsort_and_std(seed):
+    # independent route: numpy's stable argsort of the S-CAS sums, rank = inverse permutation, numpy's std
+    from tests import harness
+    L, H, K, s, R = 3, 4, 6, 2, 5
+    T = L * H
+    betas0 = [harness.random_beta(seed * 10 + r, L, H, K) for r in range(R)]
+    got = orc.rank_dispersion([orc.beta_one_based(b) for b in betas0], L, H, K, s)
+    for i in range(s + 1, K):  # 1-based source scale
+        ranks = np.empty((R, T))
+        for r, b in enumerate(betas0):
+            score = b.reshape(T, K, K).astype(np.float64)[:, i:, i - 1].sum(axis=1)  # rows tau = i+1..K (0-based i..K-1)
+            order = np.argsort(score, kind="stable")
+            ranks[r, order] = np.arange(T)
+        want = np.std(ranks, axis=0).mean()
+        assert abs(got[i] - want) < 1e-9
+    # binary variant: one CAS order for every source scale
+    gb = orc.rank_dispersion([orc.beta_one_based(b) for b in betas0], L, H, K, s, binary=True)
+    ranks = np.empty((R, T))
+    for r, b in enumerate(betas0):
+        score = b.reshape(T, K, K).astype(np.float64)[:, K - 1, s:K - 1].sum(axis=1)
+        ranks[r, np.argsort(score, kind="stable")] = np.arange(T)
+    want = np.std(ranks, axis=0).mean()
+    assert all(abs(v - want) < 1e-9 for v in gb.values())
