@@ -215,6 +215,27 @@ int heatkv_attend_append_scale(heatkv_plan* plan, int layer, int k, const void* 
                                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Head scores behind the orders O_i (Sec. 3.2): scores[i*T + head] for source scale i in [sinks, K-1) is the
+ * un-normalised sum of Eq. 4, sum over tau in (i, K) of beta[head][tau][i] (variants HEATKV and NAIVE), or of
+ * Eq. 3, sum over tau in [sinks, K-1) of beta[head][K-1][tau], the same for every i (binary variants); fp64,
+ * tau ascending, on the fp32 table handed in.  Sorting a row ascending, ties by head id, gives
+ * heatkv_plan_order.  Rows outside [sinks, K-1) are zero.  beta: host [L][H][K][K]; scores: host [K][T].
+ * Host only.  HEATKV_EINVAL for null pointers, sinks outside [0, K-2] or an unknown variant.
+ */
+int heatkv_head_scores(const heatkv_shape* shape, const float* beta, int sinks, int variant, double* scores);
+
+/*
+ * Stability of the head orders over calibration runs (App. C, S-CAS stability).  betas: host
+ * [runs][L][H][K][K], one table per run.  For every source scale i in [sinks, K-1): each run's order O_i
+ * gives each head a rank position (0 = pruned first); per head, the standard deviation of its positions
+ * around the head's own mean position (population form, divided by `runs`; the appendix does not say which);
+ * dispersion[i] = mean over the T heads.  Entries outside [sinks, K-1) are zero.  dispersion: host [K].
+ * Host only.  HEATKV_EINVAL for null pointers, runs < 1, sinks outside [0, K-2] or an unknown variant.
+ */
+int heatkv_rank_dispersion(const heatkv_shape* shape, const float* betas, int runs, int sinks, int variant,
+                           double* dispersion);
+
+/*
  * Measurement aid, not a step of the method: the bf16 matrix-core rate this GPU sustains for the caller's
  * operand bits.  Every wavefront of `workgroups` x 256 threads issues iters x 32 independent
  * v_mfma_f32_32x32x16_bf16 instructions (32768 FLOP each) on operands read once from `operands`, a device

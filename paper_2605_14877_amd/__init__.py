@@ -21,8 +21,10 @@ from .binding import (  # noqa: F401
     heatkv_build_schedule,
     heatkv_calibrate,
     heatkv_calibrate_accumulate,
+    heatkv_head_scores,
     heatkv_load_schedule,
     heatkv_probe_mfma,
+    heatkv_rank_dispersion,
     heatkv_probe_mfma_operand_bytes,
     library_path,
 )

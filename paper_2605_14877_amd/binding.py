@@ -91,6 +91,11 @@ def lib():
     L.heatkv_attend_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
     L.heatkv_attend_append_scale.restype = C.c_int
     L.heatkv_attend_append_scale.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    f64p = C.POINTER(C.c_double)
+    L.heatkv_head_scores.restype = C.c_int
+    L.heatkv_head_scores.argtypes = [sp, f32p, C.c_int, C.c_int, f64p]
+    L.heatkv_rank_dispersion.restype = C.c_int
+    L.heatkv_rank_dispersion.argtypes = [sp, f32p, C.c_int, C.c_int, C.c_int, f64p]
     L.heatkv_probe_mfma_operand_bytes.restype = C.c_size_t
     L.heatkv_probe_mfma_operand_bytes.argtypes = []
     L.heatkv_probe_mfma.restype = C.c_int
@@ -275,3 +280,21 @@ def heatkv_probe_mfma(operands, out, workgroups, iters, stream=None):
     """Measurement aid: back-to-back bf16 MFMAs on the caller's operand bits (see include/heatkv.h)."""
     _check(lib().heatkv_probe_mfma(_ptr(operands), _ptr(out), int(workgroups), int(iters),
                                    _stream() if stream is None else stream))
+
+
+def heatkv_head_scores(shape, beta, sinks, variant=VARIANT_HEATKV):
+    """[K][T] fp64 scores behind the orders (Eq. 3 / Eq. 4 sums); beta: host [L,H,K,K] float32."""
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    out = np.zeros((shape.K, shape.L * shape.H), dtype=np.float64)
+    _check(lib().heatkv_head_scores(shape.ref, beta.ctypes.data_as(C.POINTER(C.c_float)), int(sinks), int(variant),
+                                    out.ctypes.data_as(C.POINTER(C.c_double))))
+    return out
+
+
+def heatkv_rank_dispersion(shape, betas, sinks, variant=VARIANT_HEATKV):
+    """[K] fp64 rank-position dispersion over runs (App. C); betas: host [runs,L,H,K,K] float32."""
+    betas = np.ascontiguousarray(betas, dtype=np.float32)
+    out = np.zeros(shape.K, dtype=np.float64)
+    _check(lib().heatkv_rank_dispersion(shape.ref, betas.ctypes.data_as(C.POINTER(C.c_float)), int(betas.shape[0]),
+                                        int(sinks), int(variant), out.ctypes.data_as(C.POINTER(C.c_double))))
+    return out

@@ -393,6 +393,15 @@ int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const f
   return HEATKV_OK;
 }
 
+int heatkv_head_scores(const heatkv_shape* shape, const float* beta, int sinks, int variant, double* scores) {
+  return heatkv::rank_scores(shape, beta, sinks, variant, scores);
+}
+
+int heatkv_rank_dispersion(const heatkv_shape* shape, const float* betas, int runs, int sinks, int variant,
+                           double* dispersion) {
+  return heatkv::rank_dispersion(shape, betas, runs, sinks, variant, dispersion);
+}
+
 size_t heatkv_probe_mfma_operand_bytes(void) { return heatkv::probe_mfma_operand_bytes(); }
 
 int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iters, void* stream) {

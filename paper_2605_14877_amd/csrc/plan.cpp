@@ -5,6 +5,7 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <deque>
 #include <numeric>
@@ -66,6 +67,25 @@ std::vector<int32_t> rank_heads(const std::vector<double>& score) {
   return order;
 }
 
+// Head scores that the orders are built from: score[i][head] for source scale i in [s, K-1), the
+// un-normalised sums of Eq. 4 (scale-dependent) or Eq. 3 (binary: the same sum for every i); fp64, tau ascending.
+void head_scores(int K, int T, int s, bool binary, const float* beta, std::vector<std::vector<double>>& score) {
+  auto b = [&](int head, int k1, int k2) { return double(beta[(size_t(head) * K + k1) * K + k2]); };
+  score.assign(K, {});
+  if (binary) {
+    std::vector<double> sc(T, 0.0);
+    for (int head = 0; head < T; ++head)
+      for (int tau = s; tau < K - 1; ++tau) sc[head] += b(head, K - 1, tau);
+    for (int i = s; i < K - 1; ++i) score[i] = sc;
+  } else {
+    for (int i = s; i < K - 1; ++i) {
+      score[i].assign(T, 0.0);
+      for (int head = 0; head < T; ++head)
+        for (int tau = i + 1; tau < K; ++tau) score[i][head] += b(head, tau, i);
+    }
+  }
+}
+
 struct Candidate {
   int32_t layer, scale, rank, head;
   int64_t weight;  // tokens its early removal takes out of a not-yet-run layer
@@ -90,21 +110,12 @@ int build_sets(heatkv_plan* p, const float* beta) {
   if (B < int64_t(T) * cs) return fail(HEATKV_EBUDGET, "budget is smaller than the sink scales of all heads");
 
   // Orders.  beta[l][h][k1][k2]; sums in fp64, tau ascending.
-  auto b = [&](int head, int k1, int k2) { return double(beta[(size_t(head) * K + k1) * K + k2]); };
+  std::vector<std::vector<double>> score;
+  head_scores(K, T, s, binary, beta, score);
   p->orders.assign(K, {});
-  if (binary) {
-    std::vector<double> score(T, 0.0);
-    for (int head = 0; head < T; ++head)
-      for (int tau = s; tau < K - 1; ++tau) score[head] += b(head, K - 1, tau);
-    auto order = rank_heads(score);
-    for (int i = s; i < K - 1; ++i) p->orders[i] = order;
-  } else {
-    for (int i = s; i < K - 1; ++i) {
-      std::vector<double> score(T, 0.0);
-      for (int head = 0; head < T; ++head)
-        for (int tau = i + 1; tau < K; ++tau) score[head] += b(head, tau, i);
-      p->orders[i] = rank_heads(score);
-    }
+  for (int i = s; i < K - 1; ++i) {
+    if (binary && i > s) p->orders[i] = p->orders[s];
+    else p->orders[i] = rank_heads(score[i]);
   }
 
   const size_t KT = size_t(K) * T;
@@ -192,6 +203,63 @@ int build_sets(heatkv_plan* p, const float* beta) {
         if (i < s || !at(p->A, k, i, head)) m |= 1u << i;
       p->retained[size_t(k) * T + head] = m;
     }
+  return HEATKV_OK;
+}
+
+int rank_scores(const heatkv_shape* shape, const float* beta, int sinks, int variant, double* scores) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!beta || !scores) return fail(HEATKV_EINVAL, "null pointer");
+  const int K = shape->K, T = shape->L * shape->H;
+  if (sinks < 0 || sinks > K - 2) return fail(HEATKV_EINVAL, "sinks out of range");
+  if (variant < 0 || variant > 3) return fail(HEATKV_EINVAL, "unknown variant");
+  std::vector<std::vector<double>> score;
+  head_scores(K, T, sinks, (variant & 1) != 0, beta, score);
+  for (int i = 0; i < K; ++i)
+    for (int head = 0; head < T; ++head) scores[size_t(i) * T + head] = score[i].empty() ? 0.0 : score[i][head];
+  return HEATKV_OK;
+}
+
+int rank_dispersion(const heatkv_shape* shape, const float* betas, int runs, int sinks, int variant,
+                    double* dispersion) {
+  int rc = check_shape(shape);
+  if (rc) return rc;
+  if (!betas || !dispersion) return fail(HEATKV_EINVAL, "null pointer");
+  if (runs < 1) return fail(HEATKV_EINVAL, "runs must be >= 1");
+  const int K = shape->K, T = shape->L * shape->H;
+  if (sinks < 0 || sinks > K - 2) return fail(HEATKV_EINVAL, "sinks out of range");
+  if (variant < 0 || variant > 3) return fail(HEATKV_EINVAL, "unknown variant");
+  const bool binary = (variant & 1) != 0;
+  const size_t table = size_t(T) * K * K;
+  // pos[i][run][head] = rank position of the head in that run's order O_i
+  std::vector<std::vector<int32_t>> pos(K);
+  for (int r = 0; r < runs; ++r) {
+    std::vector<std::vector<double>> score;
+    head_scores(K, T, sinks, binary, betas + size_t(r) * table, score);
+    std::vector<int32_t> first;
+    for (int i = sinks; i < K - 1; ++i) {
+      if (pos[i].empty()) pos[i].assign(size_t(runs) * T, 0);
+      std::vector<int32_t> order = (binary && i > sinks) ? first : rank_heads(score[i]);
+      if (i == sinks) first = order;
+      for (int rank = 0; rank < T; ++rank) pos[i][size_t(r) * T + order[rank]] = rank;
+    }
+  }
+  for (int i = 0; i < K; ++i) dispersion[i] = 0.0;
+  for (int i = sinks; i < K - 1; ++i) {
+    double total = 0.0;
+    for (int head = 0; head < T; ++head) {
+      int64_t sum = 0;
+      for (int r = 0; r < runs; ++r) sum += pos[i][size_t(r) * T + head];
+      const double mean = double(sum) / runs;
+      double var = 0.0;
+      for (int r = 0; r < runs; ++r) {
+        const double dlt = pos[i][size_t(r) * T + head] - mean;
+        var += dlt * dlt;
+      }
+      total += std::sqrt(var / runs);
+    }
+    dispersion[i] = total / T;
+  }
   return HEATKV_OK;
 }
 

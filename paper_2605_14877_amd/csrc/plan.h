@@ -80,6 +80,11 @@ int check_shape(const heatkv_shape* shape);
 
 // Alg. 1 (+ Eq. 3-5): fills N, orders, G, E, A and `retained`.
 int build_sets(heatkv_plan* p, const float* beta);
+// Head scores behind the orders (Eq. 3 / Eq. 4, un-normalised) and the dispersion of the rank positions
+// over several calibration runs (App. C); host only, no plan involved.
+int rank_scores(const heatkv_shape* shape, const float* beta, int sinks, int variant, double* scores);
+int rank_dispersion(const heatkv_shape* shape, const float* betas, int runs, int sinks, int variant,
+                    double* dispersion);
 // Fills `retained` from an explicit pattern.
 int load_pattern(heatkv_plan* p, const uint8_t* present);
 // Derives run tables, the FIFO arena placement and the append descriptors from `retained`.

@@ -33,6 +33,16 @@ static int run_case(int L, int H, const std::vector<int32_t>& t, int sinks, int 
       for (int k2 = 0; k2 <= k1; ++k2) sum += (beta[(head * K + k1) * K + k2] = float(rnd() + 1e-3));
       for (int k2 = 0; k2 <= k1; ++k2) beta[(head * K + k1) * K + k2] /= float(sum);
     }
+  {  // the rank diagnostics walk the same table: three "runs" made of shifted copies of it
+    std::vector<float> runs(3 * beta.size());
+    for (int r = 0; r < 3; ++r)
+      for (size_t i = 0; i < beta.size(); ++i) runs[r * beta.size() + i] = beta[(i + r * 7) % beta.size()];
+    std::vector<double> sc(size_t(K) * L * H), disp(K);
+    if (sinks <= K - 2) {
+      if (heatkv::rank_scores(&shape, beta.data(), sinks, variant, sc.data())) return 8;
+      if (heatkv::rank_dispersion(&shape, runs.data(), 3, sinks, variant, disp.data())) return 9;
+    }
+  }
   int rc = heatkv::build_sets(&p, beta.data());
   if (rc == HEATKV_EBUDGET) return 0;  // legitimate outcome for tight budgets
   if (rc) return 2;

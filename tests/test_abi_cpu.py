@@ -211,3 +211,53 @@ def test_full_budget_plan_keeps_everything():
         for l in range(2):
             for h in range(2):
                 assert plan.retained(k, l, h).tolist() == list(range(c[k] - t0[k]))
+
+
+@pytest.mark.parametrize("variant", [binding.VARIANT_HEATKV, binding.VARIANT_BINARY])
+def test_head_scores_and_rank_dispersion_match_oracle(variant):
+    # App. C diagnostic and the Eq. 3 / Eq. 4 sums behind the orders, on the same fp32 beta bytes
+    L, H, sides, s, R = 3, 4, (1, 2, 3, 4, 6, 8), 2, 5
+    t0 = hi.tokens_per_scale(sides)
+    K, T = len(t0), L * H
+    shape = hk.Shape(L, H, 64, t0, 1, "f32")
+    betas0 = np.stack([harness.random_beta(40 + r, L, H, K) for r in range(R)])
+    binary = variant == binding.VARIANT_BINARY
+    # scores: sorting them (stable) reproduces the plan's orders, and they equal the oracle's sums bit for bit
+    sc = hk.heatkv_head_scores(shape, betas0[0], s, variant)
+    b1 = orc.beta_one_based(betas0[0])
+    c = hi.cumulative_tokens(t0)
+    plan = hk.heatkv_build_schedule(shape, betas0[0], T * c[-2] * 512 // 2, s, variant)
+    for i in range(s, K - 1):
+        for head in range(T):
+            l, h = head // H + 1, head % H + 1
+            want = orc.cas_sum(b1[l, h], K, s) if binary else orc.scas_sum(b1[l, h], K, i + 1)
+            assert sc[i, head] == want
+        assert np.argsort(sc[i], kind="stable").tolist() == plan.order(i).tolist()
+    assert not sc[:s].any() and not sc[K - 1:].any()
+    got = hk.heatkv_rank_dispersion(shape, betas0, s, variant)
+    want = orc.rank_dispersion([orc.beta_one_based(b) for b in betas0], L, H, K, s, binary=binary)
+    for i in range(K):
+        if s <= i < K - 1:
+            assert abs(got[i] - want[i + 1]) <= 1e-12 * max(1.0, want[i + 1])
+        else:
+            assert got[i] == 0.0
+    # one run: no dispersion; bad arguments are rejected
+    assert not hk.heatkv_rank_dispersion(shape, betas0[:1], s, variant).any()
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_rank_dispersion(shape, betas0, K - 1, variant)
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_head_scores(shape, betas0[0], s, 7)
+
+
+def test_sink_count_sweep_matches_oracle():
+    # Table 3b varies the number of sink scales s = 1..6 at a fixed budget: planner against oracle for each
+    cfg = hi.CONFIGS["layer2b"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    K, L, H = len(t0), cfg["L"], cfg["H"]
+    beta0, _ = harness.config_beta("layer2b")
+    B = hi.budget_tokens(cfg)
+    shape = hk.Shape(L, H, cfg["d"], t0, cfg["batch"], cfg["dtype"])
+    for s in range(1, 7):
+        plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * cfg["d"] * hi.elem_bytes(cfg["dtype"]), s)
+        ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
+        _compare(plan, ref, K, L, H, s)

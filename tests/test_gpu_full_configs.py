@@ -23,6 +23,7 @@ def _calibrate_stack(cfg, shape, w, t0, c, sm, n_sets, seed, rng, n_mass_samples
     """Runs heatkv_calibrate over n_sets activation sets and all layers; returns beta (host) and mass checks."""
     L, H, K, nb = cfg["L"], cfg["H"], len(t0), cfg["batch"]
     beta = torch.zeros(L, H, K, K, device=DEV)
+    beta_sets = torch.zeros(n_sets, L, H, K, K, device=DEV)  # one table per activation set (App. C runs)
     mass = torch.empty(nb, H, K, device=DEV)
     ws = [torch.empty(max(binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device=DEV)
           for k1 in range(K)]
@@ -37,11 +38,12 @@ def _calibrate_stack(cfg, shape, w, t0, c, sm, n_sets, seed, rng, n_mass_samples
                 ka = k[:, :, :c[k1]].contiguous()
                 hk.heatkv_calibrate(shape, l, k1, qk, ka, sm, mass, ws[k1])
                 hk.heatkv_accumulate_beta(shape, l, k1, mass, 1.0 / (n_sets * nb), beta)
+                hk.heatkv_accumulate_beta(shape, l, k1, mass, 1.0 / nb, beta_sets[st])
                 if (st, l, k1) in picks:
                     b, h = int(rng.integers(nb)), int(rng.integers(H))
                     checks.append((k1, mass[b, h].cpu().double().numpy(), q[b, h].cpu(), k[b, h].cpu()))
     torch.cuda.synchronize()
-    return beta.cpu().numpy(), checks
+    return beta.cpu().numpy(), checks, beta_sets.cpu().numpy()
 
 
 def _run_stack(name, layers, n_calib_sets, seed, n_samples, rows_per_sample=24):
@@ -58,11 +60,19 @@ def _run_stack(name, layers, n_calib_sets, seed, n_samples, rows_per_sample=24):
     t1 = orc.one_based(t0)
 
     if n_calib_sets:
-        beta_h, checks = _calibrate_stack(cfg, shape, w, t0, c, sm, n_calib_sets, seed, rng, 10)
+        beta_h, checks, beta_sets = _calibrate_stack(cfg, shape, w, t0, c, sm, n_calib_sets, seed, rng, 10)
         for k1, got, q_bh, k_bh in checks:
             want = orc.beta_row(q_bh.double().numpy(), k_bh.double().numpy(), t1, k1 + 1, sm)[1:]
             assert np.abs(got - want).max() <= 1e-4, (name, k1)
         assert np.abs(beta_h.sum(-1) - 1.0).max() <= 1e-4
+        # Stability of the head orders over the activation sets (App. C): library against oracle on the same
+        # per-set beta bytes; the figure itself is reported as a fraction of the ordering range T.
+        disp = hk.heatkv_rank_dispersion(shape, beta_sets, s)
+        want = orc.rank_dispersion([orc.beta_one_based(b) for b in beta_sets], L, H, K, s)
+        for i in range(s, K - 1):
+            assert abs(disp[i] - want[i + 1]) <= 1e-9 * max(1.0, want[i + 1])
+        print(f"{name}: rank dispersion over {n_calib_sets} sets, % of T={L * H} per source scale:",
+              np.round(100.0 * disp[s:K - 1] / (L * H), 3).tolist())
     else:
         beta_h = hi.expected_beta_from_weights(w, t0).astype(np.float32)
 

@@ -249,3 +249,36 @@ def test_mfma_probe_runs_and_is_deterministic():
     assert (out1 == 0).all()
     with pytest.raises(hk.HeatKVError):
         hk.heatkv_probe_mfma(ops, out1, 0, 3)
+
+
+def test_rank_dispersion_over_gpu_calibration_runs():
+    # App. C on synthetic data: three seeded activation sets of one small stack, beta of each from the GPU
+    # calibration pass, head-rank dispersion from the library against the oracle on the same beta bytes.
+    sides, L, H, d, batch, s = (1, 2, 4, 6, 8, 12), 2, 3, 128, 2, 2
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K = len(t0)
+    sm = 1.0 / np.sqrt(d)
+    cfg = dict(L=L, H=H, d=d, dtype="bf16", batch=batch, sides=sides)
+    w = hi.head_weights(6, L, H, K)
+    shape = hk.Shape(L, H, d, t0, batch, "bf16")
+    betas = []
+    for run in range(3):
+        beta = torch.zeros(L, H, K, K, device="cuda")
+        for l in range(L):
+            q, k, _ = hi.make_qkv(100 + run, l, cfg, w=w)
+            dq, dk = _dev(q, k)
+            for k1 in range(K):
+                qk = dq[:, :, c[k1] - t0[k1]:c[k1]].contiguous()
+                ka = dk[:, :, :c[k1]].contiguous()
+                ws = torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device="cuda")
+                hk.heatkv_calibrate_accumulate(shape, l, k1, qk, ka, sm, 1.0 / batch, beta, None, ws)
+        betas.append(beta.cpu().numpy())
+    betas = np.stack(betas)
+    got = hk.heatkv_rank_dispersion(shape, betas, s)
+    want = orc.rank_dispersion([orc.beta_one_based(b) for b in betas], L, H, K, s)
+    for i in range(s, K - 1):
+        assert abs(got[i] - want[i + 1]) <= 1e-12 * max(1.0, want[i + 1])
+    # the planted per-head preferences dominate the sampling noise: heads keep their places
+    print("rank dispersion per source scale (heads:", L * H, "):", got[s:K - 1])
+    assert got.max() <= 0.25 * L * H
