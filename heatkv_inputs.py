@@ -23,8 +23,8 @@ SIDES_TINY = (1, 2, 4, 8)
 
 
 def tokens_per_scale(sides):
-    """t_k = h_k * w_k for square token maps (Sec. 3.1 notation)."""
-    return [int(s) * int(s) for s in sides]
+    """t_k = h_k * w_k (Sec. 3.1 notation); an entry is a side s (square map, s * s tokens) or a pair (h, w)."""
+    return [int(s[0]) * int(s[1]) if isinstance(s, (tuple, list)) else int(s) * int(s) for s in sides]
 
 
 def cumulative_tokens(t):

@@ -149,6 +149,12 @@ def test_bf16_small_ragged_scales():
     _bf16_case(1, 4, (1, 2, 4, 6, 8, 11, 13), 3, 3, 2, seed=2)
 
 
+def test_bf16_non_square_token_maps():
+    # a 2:1 pyramid (h x 2h token maps), token counts that are no squares and no multiples of the tile sizes
+    sides = ((1, 2), (2, 3), (3, 6), (5, 10), (7, 13), (9, 19), (12, 23))
+    _bf16_case(2, 3, sides, 2, 3, 2, seed=8, fused=True)
+
+
 def test_bf16_fused_attend_append_medium():
     # attend + append in one launch, scales up to 32x32 tokens, several key tiles per head
     _bf16_case(1, 6, (1, 2, 4, 6, 8, 12, 16, 20, 24, 32), 3, 4, 2, seed=5, fused=True)
