@@ -19,9 +19,12 @@ total-cache identity; Alg. 1 against a hand-worked example
 for the binary variant, brute-force minimum cardinality (Prop. 1); the rank
 dispersion of App. C against closed forms (identical runs, reversed orders)
 and against numpy's argsort/std on random tables.
-Parity unpinned: minimum cardinality of E_k in the scale-dependent variant
-(the paper proves it for the binary case only); there only the algorithm's
-steps are followed.
+Minimum cardinality of E_k is not a property of the scale-dependent variant
+(the paper proves it for the binary case only): a hand-worked instance,
+tests/golden/alg1_scale_dependent_not_minimal.txt, has the printed greedy
+order pop three head-scales where two suffice.  There the algorithm's steps
+are followed as printed and pinned by the two hand-worked examples and the
+invariants.  No function of this file is left without a pin.
 """
 from __future__ import annotations
 

@@ -261,3 +261,21 @@ def test_sink_count_sweep_matches_oracle():
         plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * cfg["d"] * hi.elem_bytes(cfg["dtype"]), s)
         ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
         _compare(plan, ref, K, L, H, s)
+
+
+def test_library_follows_printed_greedy_order_where_it_is_not_minimal():
+    # the instance of tests/golden/alg1_scale_dependent_not_minimal.txt: the planner pops three head-scales
+    # exactly as the printed sort dictates, although two would do
+    L, H, s, B = 3, 1, 1, 15
+    t0 = [1, 4, 9, 16]
+    K = len(t0)
+    beta0 = np.zeros((L, H, K, K), dtype=np.float32)
+    for l in range(L):
+        beta0[l, 0, 3, 1] = beta0[l, 0, 3, 2] = beta0[l, 0, 2, 1] = 0.1 * (l + 1)  # heads ranked (1,1) < (2,1) < (3,1)
+    shape = hk.Shape(L, H, 64, t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * 64 * 4, s)
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, B)
+    _compare(plan, ref, K, L, H, s)
+    E = plan.sets(2, binding.SET_E)  # 0-based scale 2 = paper scale 3; bitmap [source scale][head]
+    got = sorted((i + 1, head // H + 1, head % H + 1) for i in range(K) for head in range(L * H) if E[i, head])
+    assert got == [(2, 3, 1), (3, 2, 1), (3, 3, 1)]

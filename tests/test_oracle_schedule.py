@@ -315,3 +315,38 @@ def test_rank_dispersion_against_numpy_argsort_and_std(seed):
         ranks[r, np.argsort(score, kind="stable")] = np.arange(T)
     want = np.std(ranks, axis=0).mean()
     assert all(abs(v - want) < 1e-9 for v in gb.values())
+
+
+def test_scale_dependent_greedy_is_not_minimum_cardinality():
+    # The paper proves minimum cardinality of E_k for the binary variant only.  This hand-worked instance
+    # (tests/golden/alg1_scale_dependent_not_minimal.txt) shows that the scale-dependent variant, followed as
+    # printed, can pop more elements than necessary; the oracle must reproduce the printed order, not repair it.
+    path = os.path.join(os.path.dirname(__file__), "golden", "alg1_scale_dependent_not_minimal.txt")
+    rec = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *rest = line.split()
+        rec[key] = rest
+    items = lambda toks: [tuple(int(x) for x in tok.split(",")) for tok in toks]
+    L, H, s, B = 3, 1, 1, 15
+    t = orc.one_based([1, 4, 9, 16])
+    c = orc.cumulative(t)
+    K, T = 4, L * H
+    N = orc.heads_to_prune(T, t, s, B)
+    assert N[1:] == [int(x) for x in rec["N"]]
+    order = [(1, 1), (2, 1), (3, 1)]
+    sch = orc.heatkv_schedule({2: order, 3: order}, N, t, s, L, H, B)
+    k = int(rec["GREEDY_E"][0])
+    assert sorted(sch["E"][k].items()) == sorted(items(rec["GREEDY_E"][1:]))
+    Gp = sch["G"][k - 1]
+    sizes = lambda E: [orc.cache_size_after_layer(k, l, sch["G"][k], Gp, orc._Sets(K, L, H, E), t, c, s, L, H)
+                       for l in range(1, L + 1)]
+    assert sizes(items(rec["GREEDY_E"][1:])) == [int(x) for x in rec["SIZES_GREEDY"]]
+    smaller = items(rec["SMALLER_FEASIBLE_E"][1:])
+    assert sizes(smaller) == [int(x) for x in rec["SIZES_SMALLER"]] and max(sizes(smaller)) <= B
+    assert len(smaller) < len(sch["E"][k])
+    # brute force agrees that 2 is the minimum
+    cand = [it for it in sch["G"][k].items() if it not in Gp]
+    best = min(r for r in range(len(cand) + 1) for sub in itertools.combinations(cand, r) if max(sizes(sub)) <= B)
+    assert best == len(smaller)
