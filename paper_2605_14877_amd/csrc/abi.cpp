@@ -41,7 +41,12 @@ int ensure_uploaded(heatkv_plan* p) {
   const size_t nd = p->descs.size() * sizeof(heatkv::CopyDesc);
   const size_t o_row = 0, o_len = o_row + pad(n3), o_ord = o_len + pad(n3), o_desc = o_ord + pad(n3);
   const size_t total = o_desc + pad(nd) + 16;
-  std::vector<unsigned char> host(total, 0);
+  std::vector<unsigned char> host;
+  try {
+    host.assign(total, 0);
+  } catch (const std::bad_alloc&) {
+    return fail(HEATKV_ENOMEM, "out of host memory");
+  }
   std::memcpy(host.data() + o_row, p->run_row.data(), n3);
   std::memcpy(host.data() + o_len, p->run_len.data(), n3);
   std::memcpy(host.data() + o_ord, p->head_order.data(), n3);
@@ -394,12 +399,20 @@ int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const f
 }
 
 int heatkv_head_scores(const heatkv_shape* shape, const float* beta, int sinks, int variant, double* scores) {
-  return heatkv::rank_scores(shape, beta, sinks, variant, scores);
+  try {
+    return heatkv::rank_scores(shape, beta, sinks, variant, scores);
+  } catch (const std::bad_alloc&) {
+    return fail(HEATKV_ENOMEM, "out of host memory");
+  }
 }
 
 int heatkv_rank_dispersion(const heatkv_shape* shape, const float* betas, int runs, int sinks, int variant,
                            double* dispersion) {
-  return heatkv::rank_dispersion(shape, betas, runs, sinks, variant, dispersion);
+  try {
+    return heatkv::rank_dispersion(shape, betas, runs, sinks, variant, dispersion);
+  } catch (const std::bad_alloc&) {
+    return fail(HEATKV_ENOMEM, "out of host memory");
+  }
 }
 
 size_t heatkv_probe_mfma_operand_bytes(void) { return heatkv::probe_mfma_operand_bytes(); }
