@@ -138,8 +138,52 @@ def _ptr(x):
         return None
     if isinstance(x, np.ndarray):
         return x.ctypes.data
-    assert x.is_contiguous()
+    if not x.is_contiguous():
+        raise ValueError("tensor must be contiguous")
     return x.data_ptr()
+
+
+# The kernels trust the sizes the plan / shape imply, so the operands are checked here, on the host, before
+# any pointer crosses the boundary: a wrong tensor becomes a Python error, not a memory fault on the GPU.
+def _check_tensor(x, name, shape=None, dtype_code=None, min_bytes=None):
+    import torch
+    if x is None:
+        return
+    if not isinstance(x, torch.Tensor):
+        raise TypeError(f"{name}: expected a torch tensor")
+    if not x.is_cuda:
+        raise ValueError(f"{name}: expected a device tensor")
+    if not x.is_contiguous():
+        raise ValueError(f"{name}: tensor must be contiguous")
+    if shape is not None and tuple(x.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(x.shape)} does not match {tuple(shape)}")
+    if dtype_code is not None:
+        want = torch.bfloat16 if dtype_code == BF16 else torch.float32
+        if x.dtype != want:
+            raise ValueError(f"{name}: dtype {x.dtype} does not match {want}")
+    if min_bytes is not None and x.numel() * x.element_size() < min_bytes:
+        raise ValueError(f"{name}: {x.numel() * x.element_size()} bytes, at least {min_bytes} needed")
+
+
+def _check_scale_operands(plan, layer, k, named, arenas):
+    sh = plan.shape
+    if not (0 <= layer < sh.L and 0 <= k < sh.K):
+        return  # the library reports the index error
+    cur = (sh.batch, sh.H, int(sh.t[k]), sh.d)
+    for name, x in named:
+        _check_tensor(x, name, cur, sh.dtype)
+    for name, x in arenas:
+        _check_tensor(x, name, min_bytes=plan.arena_bytes)
+
+
+def _check_calibrate_operands(shape, k1, q, k_all, mass, beta):
+    if not 0 <= k1 < shape.K:
+        return
+    t_k, c_k = int(shape.t[k1]), int(shape.t[: k1 + 1].sum())
+    _check_tensor(q, "q", (shape.batch, shape.H, t_k, shape.d), shape.dtype)
+    _check_tensor(k_all, "k_all", (shape.batch, shape.H, c_k, shape.d), shape.dtype)
+    _check_tensor(mass, "mass", (shape.batch, shape.H, shape.K), F32)
+    _check_tensor(beta, "beta", (shape.L, shape.H, shape.K, shape.K), F32)
 
 
 def _stream():
@@ -233,6 +277,8 @@ def calibrate_workspace_bytes(shape, k1):
 
 
 def heatkv_calibrate(shape, layer, k1, q, k_all, sm_scale, mass, ws, stream=None):
+    _check_calibrate_operands(shape, k1, q, k_all, mass, None)
+    _check_tensor(ws, "ws")
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().heatkv_calibrate(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale), _ptr(mass),
                                   _ptr(ws), ws_bytes, _stream() if stream is None else stream))
@@ -242,16 +288,22 @@ calibrate = heatkv_calibrate
 
 
 def heatkv_accumulate_beta(shape, layer, k1, mass, weight, beta, stream=None):
+    _check_calibrate_operands(shape, k1, None, None, mass, beta)
     _check(lib().heatkv_accumulate_beta(shape.ref, layer, k1, _ptr(mass), float(weight), _ptr(beta),
                                         _stream() if stream is None else stream))
 
 
 def heatkv_append_scale(plan, layer, k, k_new, v_new, k_arena, v_arena, stream=None):
+    _check_scale_operands(plan, layer, k, (("k_new", k_new), ("v_new", v_new)),
+                          (("k_arena", k_arena), ("v_arena", v_arena)))
     _check(lib().heatkv_append_scale(plan.handle, layer, k, _ptr(k_new), _ptr(v_new), _ptr(k_arena), _ptr(v_arena),
                                      _stream() if stream is None else stream))
 
 
 def heatkv_attend_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, sm_scale, out, ws=None, stream=None):
+    _check_scale_operands(plan, layer, k, (("q", q), ("k_cur", k_cur), ("v_cur", v_cur), ("out", out)),
+                          (("k_arena", k_arena), ("v_arena", v_arena)))
+    _check_tensor(ws, "ws")
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().heatkv_attend_scale(plan.handle, layer, k, _ptr(q), _ptr(k_cur), _ptr(v_cur), _ptr(k_arena),
                                      _ptr(v_arena), float(sm_scale), _ptr(out), _ptr(ws), ws_bytes,
@@ -259,6 +311,9 @@ def heatkv_attend_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, sm_sc
 
 
 def heatkv_attend_append_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena, sm_scale, out, ws=None, stream=None):
+    _check_scale_operands(plan, layer, k, (("q", q), ("k_cur", k_cur), ("v_cur", v_cur), ("out", out)),
+                          (("k_arena", k_arena), ("v_arena", v_arena)))
+    _check_tensor(ws, "ws")
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().heatkv_attend_append_scale(plan.handle, layer, k, _ptr(q), _ptr(k_cur), _ptr(v_cur), _ptr(k_arena),
                                             _ptr(v_arena), float(sm_scale), _ptr(out), _ptr(ws), ws_bytes,
@@ -266,6 +321,8 @@ def heatkv_attend_append_scale(plan, layer, k, q, k_cur, v_cur, k_arena, v_arena
 
 
 def heatkv_calibrate_accumulate(shape, layer, k1, q, k_all, sm_scale, weight, beta, mass, ws, stream=None):
+    _check_calibrate_operands(shape, k1, q, k_all, mass, beta)
+    _check_tensor(ws, "ws")
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().heatkv_calibrate_accumulate(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale),
                                              float(weight), _ptr(beta), _ptr(mass), _ptr(ws), ws_bytes,
@@ -278,6 +335,8 @@ def heatkv_probe_mfma_operand_bytes():
 
 def heatkv_probe_mfma(operands, out, workgroups, iters, stream=None):
     """Measurement aid: back-to-back bf16 MFMAs on the caller's operand bits (see include/heatkv.h)."""
+    _check_tensor(operands, "operands", min_bytes=heatkv_probe_mfma_operand_bytes())
+    _check_tensor(out, "out", min_bytes=max(int(workgroups), 0) * 256 * 4)
     _check(lib().heatkv_probe_mfma(_ptr(operands), _ptr(out), int(workgroups), int(iters),
                                    _stream() if stream is None else stream))
 

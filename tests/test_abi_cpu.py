@@ -279,3 +279,20 @@ def test_library_follows_printed_greedy_order_where_it_is_not_minimal():
     E = plan.sets(2, binding.SET_E)  # 0-based scale 2 = paper scale 3; bitmap [source scale][head]
     got = sorted((i + 1, head // H + 1, head % H + 1) for i in range(K) for head in range(L * H) if E[i, head])
     assert got == [(2, 3, 1), (3, 2, 1), (3, 3, 1)]
+
+
+def test_binding_rejects_wrong_operands_before_any_gpu_call():
+    # the kernels trust the plan's sizes; the binding checks tensors on the host (device, shape, dtype, size)
+    import torch
+    t0 = hi.tokens_per_scale(hi.SIDES_TINY)
+    shape = hk.Shape(1, 4, 64, t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, harness.random_beta(1, 1, 4, 4), 42 * 512, 1)
+    good = torch.zeros(1, 4, t0[1], 64)  # right shape and dtype, but host memory
+    with pytest.raises(ValueError, match="device tensor"):
+        hk.heatkv_attend_scale(plan, 0, 1, good, good, good, good, good, 0.125, good, stream=0)
+    with pytest.raises(ValueError, match="device tensor"):
+        hk.heatkv_append_scale(plan, 0, 1, good, good, good, good, stream=0)
+    with pytest.raises(TypeError):
+        hk.heatkv_attend_scale(plan, 0, 1, np.zeros(4), None, None, None, None, 0.125, None, stream=0)
+    with pytest.raises(ValueError, match="device tensor"):
+        hk.heatkv_calibrate(shape, 0, 1, good, good, 0.125, good, None, stream=0)

@@ -288,3 +288,21 @@ def test_rank_dispersion_over_gpu_calibration_runs():
     # the planted per-head preferences dominate the sampling noise: heads keep their places
     print("rank dispersion per source scale (heads:", L * H, "):", got[s:K - 1])
     assert got.max() <= 0.25 * L * H
+
+
+def test_binding_rejects_wrong_shapes_and_dtypes_on_device():
+    t0 = hi.tokens_per_scale(hi.SIDES_TINY)
+    shape = hk.Shape(1, 4, 64, t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, harness.random_beta(1, 1, 4, 4), 42 * 512, 1)
+    ok = torch.zeros(1, 4, t0[2], 64, device="cuda")
+    arena = torch.zeros(max(plan.arena_bytes, 16), dtype=torch.uint8, device="cuda")
+    with pytest.raises(ValueError, match="shape"):
+        hk.heatkv_attend_scale(plan, 0, 2, ok[:, :, :3].contiguous(), ok, ok, arena, arena, 0.125, ok)
+    with pytest.raises(ValueError, match="dtype"):
+        hk.heatkv_attend_scale(plan, 0, 2, ok.to(torch.bfloat16), ok, ok, arena, arena, 0.125, ok)
+    with pytest.raises(ValueError, match="bytes"):
+        hk.heatkv_attend_scale(plan, 0, 2, ok, ok, ok, arena[:8], arena, 0.125, ok)
+    with pytest.raises(ValueError, match="contiguous"):
+        hk.heatkv_attend_scale(plan, 0, 2, ok.transpose(1, 2).contiguous().transpose(1, 2), ok, ok, arena, arena, 0.125, ok)
+    hk.heatkv_attend_scale(plan, 0, 2, ok, ok, ok, arena, arena, 0.125, ok)  # the well-formed call goes through
+    torch.cuda.synchronize()
