@@ -27,6 +27,7 @@ class _CShape(C.Structure):
 
 
 _lib = None
+_torch = None
 
 
 def library_path():
@@ -42,7 +43,9 @@ def lib():
         raise ImportError(f"{_LIB_PATH} is not built; run `python -m paper_2605_14877_amd.build`")
     # The library must share PyTorch's HIP runtime (streams and device pointers cross the boundary):
     # importing torch first makes its libamdhip64.so.7 the one the dynamic linker binds us to.
-    import torch  # noqa: F401
+    import torch
+    global _torch
+    _torch = torch
     L = C.CDLL(_LIB_PATH)
     vp, i32p, u8p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.POINTER(C.c_float)
     sp = C.POINTER(_CShape)
@@ -146,21 +149,19 @@ def _ptr(x):
 # The kernels trust the sizes the plan / shape imply, so the operands are checked here, on the host, before
 # any pointer crosses the boundary: a wrong tensor becomes a Python error, not a memory fault on the GPU.
 def _check_tensor(x, name, shape=None, dtype_code=None, min_bytes=None):
-    import torch
     if x is None:
         return
+    torch = _torch
     if not isinstance(x, torch.Tensor):
         raise TypeError(f"{name}: expected a torch tensor")
     if not x.is_cuda:
         raise ValueError(f"{name}: expected a device tensor")
     if not x.is_contiguous():
         raise ValueError(f"{name}: tensor must be contiguous")
-    if shape is not None and tuple(x.shape) != tuple(shape):
+    if shape is not None and x.shape != shape:
         raise ValueError(f"{name}: shape {tuple(x.shape)} does not match {tuple(shape)}")
-    if dtype_code is not None:
-        want = torch.bfloat16 if dtype_code == BF16 else torch.float32
-        if x.dtype != want:
-            raise ValueError(f"{name}: dtype {x.dtype} does not match {want}")
+    if dtype_code is not None and x.dtype is not (torch.bfloat16 if dtype_code == BF16 else torch.float32):
+        raise ValueError(f"{name}: dtype {x.dtype} does not match the plan's")
     if min_bytes is not None and x.numel() * x.element_size() < min_bytes:
         raise ValueError(f"{name}: {x.numel() * x.element_size()} bytes, at least {min_bytes} needed")
 
@@ -169,11 +170,13 @@ def _check_scale_operands(plan, layer, k, named, arenas):
     sh = plan.shape
     if not (0 <= layer < sh.L and 0 <= k < sh.K):
         return  # the library reports the index error
-    cur = (sh.batch, sh.H, int(sh.t[k]), sh.d)
+    cur = plan.scale_shapes[k]
+    dt = sh.dtype
     for name, x in named:
-        _check_tensor(x, name, cur, sh.dtype)
+        _check_tensor(x, name, cur, dt)
+    nbytes = plan.arena_bytes_cached
     for name, x in arenas:
-        _check_tensor(x, name, min_bytes=plan.arena_bytes)
+        _check_tensor(x, name, None, None, nbytes)
 
 
 def _check_calibrate_operands(shape, k1, q, k_all, mass, beta):
@@ -197,6 +200,9 @@ class Plan:
     def __init__(self, handle, shape):
         self.handle = C.c_void_p(handle)
         self.shape = shape
+        # what the per-scale tensors and the arenas must look like (checked by the wrappers on every call)
+        self.scale_shapes = [(shape.batch, shape.H, int(t), shape.d) for t in shape.t]
+        self.arena_bytes_cached = int(lib().heatkv_plan_arena_bytes(self.handle))
 
     def __del__(self):
         if getattr(self, "handle", None) and _lib is not None:
