@@ -306,3 +306,52 @@ def test_binding_rejects_wrong_shapes_and_dtypes_on_device():
         hk.heatkv_attend_scale(plan, 0, 2, ok.transpose(1, 2).contiguous().transpose(1, 2), ok, ok, arena, arena, 0.125, ok)
     hk.heatkv_attend_scale(plan, 0, 2, ok, ok, ok, arena, arena, 0.125, ok)  # the well-formed call goes through
     torch.cuda.synchronize()
+
+
+def test_generation_pass_replays_from_a_hip_graph():
+    # Once the plan is uploaded the entry points only enqueue kernels on the caller's stream, so a whole
+    # generation pass can be captured and replayed; every replay must reproduce the eager results bit for bit,
+    # also with other work and synchronisations between the replays.
+    sides, L, H, d, batch, s = (1, 2, 4, 6, 8, 12, 16), 1, 4, 128, 2, 2
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K = len(t0)
+    sm = 1.0 / np.sqrt(d)
+    cfg = dict(L=L, H=H, d=d, dtype="bf16", batch=batch, sides=sides)
+    w = hi.head_weights(12, L, H, K)
+    beta0 = hi.expected_beta_from_weights(w, t0).astype(np.float32)
+    shape = hk.Shape(L, H, d, t0, batch, "bf16")
+    plan = hk.heatkv_build_schedule(shape, beta0, (L * H * c[-2] // 3) * 2 * d * 2, s)
+    plan.upload()
+    q, k, v = _dev(*hi.make_qkv(12, 0, cfg, w=w))
+    sl = [slice(c[i] - t0[i], c[i]) for i in range(K)]
+    q_s = [q[:, :, x].contiguous() for x in sl]
+    k_s = [k[:, :, x].contiguous() for x in sl]
+    v_s = [v[:, :, x].contiguous() for x in sl]
+    ka = torch.zeros(max(plan.arena_bytes, 16), dtype=torch.uint8, device="cuda")
+    va = torch.zeros_like(ka)
+    outs = [torch.empty_like(x) for x in q_s]
+
+    def one_pass():
+        for kk in range(K):
+            hk.heatkv_attend_append_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, outs[kk])
+
+    one_pass()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            one_pass()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        ka.random_(0, 255)  # stale arena contents must not matter: every region is rewritten before it is read
+        va.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(outs, eager):
+            assert torch.equal(a, b), rep
