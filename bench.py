@@ -230,7 +230,12 @@ def main():
     }
 
     if not args.no_mfma_probe:
-        result["roofline"]["mfma_probe"] = mfma_probe(dev)
+        probe = mfma_probe(dev)
+        result["roofline"]["mfma_probe"] = probe
+        # the same achieved figure against what the bare matrix pipes sustain on random operands on this GPU
+        result["roofline"]["frac_of_probe_random"] = round(att_tflops / probe["random_operands"], 4)
+        result["roofline"]["largest_scale_frac_of_probe_random"] = round(
+            att_flops[K - 1] / (att_ms_k[K - 1] * 1e-3) / 1e12 / probe["random_operands"], 4)
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -371,7 +376,9 @@ def run_stack(args, dev):
                      "frac": round(float(value) / PEAK_BF16_TFLOPS, 4), "traffic": None},
     }
     if not args.no_mfma_probe:
-        result["roofline"]["mfma_probe"] = mfma_probe(dev)
+        probe = mfma_probe(dev)
+        result["roofline"]["mfma_probe"] = probe
+        result["roofline"]["frac_of_probe_random"] = round(float(value) / probe["random_operands"], 4)
     print(json.dumps(result))
 
 
