@@ -154,22 +154,40 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
         for (int r = 0; r < 16; ++r)
           if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
     }
-    float mx = s[0][0];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
-    mx = max_halves(mx);
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = fast_exp2((m_run - m_new) * c);
-    const float mc = m_new * c;
-    m_run = m_new;
+    // Probabilities are taken relative to the running reference m_run, which is only brought up to the true
+    // row maximum when it has fallen too far behind: as long as no score exceeds it by more than 8 in the
+    // base-2 exponent a lane's 32 probabilities of the tile sum to at most 2^13, so a larger sum, an infinity or
+    // a NaN (the first tile, where m_run is still -inf) sends the whole wavefront through the exact path, which
+    // finds the tile maximum, rescales what the block has summed so far and redoes the tile's exponentials.
+    // The masses are ratios of such sums, so they do not depend on the reference; the max chain, one vector
+    // instruction per two scores, leaves the common path.
+    float mc = m_run * c;
     float rs[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) rs[r & 3] += fast_exp2(fmaf(s[cb][r], c, -mc));
-    cur = fmaf(cur, alpha, (rs[0] + rs[1]) + (rs[2] + rs[3]));
+    float tile_sum = (rs[0] + rs[1]) + (rs[2] + rs[3]);
+    if (__any(!(tile_sum <= 8192.f))) {
+      float mx = s[0][0];
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
+      mx = max_halves(mx);
+      const float m_new = fmaxf(m_run, mx);
+      cur *= fast_exp2((m_run - m_new) * c);
+      m_run = m_new;
+      mc = m_new * c;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) rs[i] = 0.f;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rs[r & 3] += fast_exp2(fmaf(s[cb][r], c, -mc));
+      tile_sum = (rs[0] + rs[1]) + (rs[2] + rs[3]);
+    }
+    cur += tile_sum;
 
     if (last_of_block) {
       const float both = sum_halves(cur);

@@ -355,3 +355,34 @@ def test_generation_pass_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         for a, b in zip(outs, eager):
             assert torch.equal(a, b), rep
+
+
+def test_bf16_calibrate_rising_and_falling_logits():
+    # The calibration kernel keeps a lazy softmax reference; logits that climb steadily along the key blocks
+    # (head 0) force the exact path again and again in the middle of a walk, head 1 sees them falling.
+    sides = (1, 2, 4, 8, 16, 24)
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K, H, d, batch = len(t0), 2, 128, 1
+    sm = 1.0 / np.sqrt(d)
+    g = torch.Generator().manual_seed(23)
+    q = 0.1 * torch.randn(batch, H, c[-1], d, generator=g)
+    k = 0.1 * torch.randn(batch, H, c[-1], d, generator=g)
+    k[:, :, :, 0] = torch.linspace(-20.0, 20.0, c[-1])  # keys are walked in sequence order here
+    q[:, 0, :, 0] = 16.0
+    q[:, 1, :, 0] = -16.0
+    q, k = q.to(torch.bfloat16), k.to(torch.bfloat16)
+    dq, dk = _dev(q, k)
+    shape = hk.Shape(1, H, d, t0, batch, "bf16")
+    t1 = orc.one_based(t0)
+    for k1 in range(K):
+        qk = dq[:, :, c[k1] - t0[k1]:c[k1]].contiguous()
+        ka = dk[:, :, :c[k1]].contiguous()
+        mass = torch.full((batch, H, K), -1.0, device="cuda")
+        ws = torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device="cuda")
+        hk.heatkv_calibrate(shape, 0, k1, qk, ka, sm, mass, ws)
+        got = mass.cpu().double().numpy()
+        assert np.isfinite(got).all()
+        for h in range(H):
+            want = orc.beta_row(q[0, h].double().numpy(), k[0, h].double().numpy(), t1, k1 + 1, sm)[1:]
+            assert np.abs(got[0, h] - want).max() <= 1e-4, (k1, h, np.abs(got[0, h] - want).max())
