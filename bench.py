@@ -108,7 +108,9 @@ def main():
 
     def calibrate_and_plan():
         beta.zero_()
-        for k1 in range(K):
+        # the scales of a calibration pass are independent (each fills its own row of beta): largest first, so
+        # that the GPU is busy with the long kernels while the host enqueues the short ones
+        for k1 in reversed(range(K)):
             hk.heatkv_calibrate_accumulate(shape, 0, k1, q_s[k1], kall_s[k1], sm, 1.0 / nb, beta, mass, cal_ws[k1])
         beta_h = beta.cpu().numpy()
         plan = hk.heatkv_build_schedule(shape, beta_h, budget_bytes, s)
