@@ -279,6 +279,21 @@ def mfma_probe(dev):
             ms = e0.elapsed_time(e1)
             best = ms if best is None else min(best, ms)
         res[name] = round(flop / best / 1e9, 1)
+    # the attention kernel's tile step without its bookkeeping (same instruction mix, dependencies, LDS tiles,
+    # barrier and tile copies, random bf16 tiles served from L2): what that mix sustains on this GPU
+    tiles = torch.randn(hk.heatkv_probe_tile_step_bytes() // 2, device=dev, generator=g).to(torch.bfloat16)
+    t_iters = 600
+    out2 = torch.empty(workgroups * 256, dtype=torch.float32, device=dev)
+    best = None
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        hk.heatkv_probe_tile_step(tiles, out2, workgroups, t_iters)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    res["attention_tile_step_model"] = round(workgroups * 4 * t_iters * 32 * 32768.0 / best / 1e9, 1)
     return res
 
 

@@ -248,6 +248,20 @@ int heatkv_rank_dispersion(const heatkv_shape* shape, const float* betas, int ru
 size_t heatkv_probe_mfma_operand_bytes(void);
 int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iters, void* stream);
 
+/*
+ * Measurement aid, not a step of the method: a model of one tile step of the bf16 attention kernel.  Every
+ * wavefront of `workgroups` x 256 threads runs `iters` (even) steps, each with the kernel's instruction mix and
+ * dependencies for a 64-key tile (16 score MFMAs fed from an LDS K tile, 32 scale FMAs, 32 exp2, 16 packs, 16
+ * pair sums, 16 PV MFMAs fed from an LDS V tile, a max chain, one barrier, the copies of the next K and V tiles
+ * into LDS) and none of its bookkeeping; all workgroups stream the same heatkv_probe_tile_step_bytes() bytes of
+ * bf16 tile data from `tiles` (device, caller-filled), so the copies come from L2.  What it computes has no
+ * meaning; its rate, workgroups * 4 * iters * 32 * 32768 FLOP over the time the caller measures, is what this
+ * mix sustains on the GPU at hand.  `out`: device, workgroups x 256 floats.  Two workgroups fit a compute unit
+ * (64 KB of LDS each).  HEATKV_EINVAL for null pointers, non-positive sizes or odd iters.
+ */
+size_t heatkv_probe_tile_step_bytes(void);
+int heatkv_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

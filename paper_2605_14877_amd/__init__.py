@@ -26,5 +26,7 @@ from .binding import (  # noqa: F401
     heatkv_probe_mfma,
     heatkv_rank_dispersion,
     heatkv_probe_mfma_operand_bytes,
+    heatkv_probe_tile_step,
+    heatkv_probe_tile_step_bytes,
     library_path,
 )

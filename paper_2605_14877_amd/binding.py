@@ -103,6 +103,10 @@ def lib():
     L.heatkv_probe_mfma_operand_bytes.argtypes = []
     L.heatkv_probe_mfma.restype = C.c_int
     L.heatkv_probe_mfma.argtypes = [vp, vp, C.c_int, C.c_int, vp]
+    L.heatkv_probe_tile_step_bytes.restype = C.c_size_t
+    L.heatkv_probe_tile_step_bytes.argtypes = []
+    L.heatkv_probe_tile_step.restype = C.c_int
+    L.heatkv_probe_tile_step.argtypes = [vp, vp, C.c_int, C.c_int, vp]
     _lib = L
     return L
 
@@ -363,3 +367,15 @@ def heatkv_rank_dispersion(shape, betas, sinks, variant=VARIANT_HEATKV):
     _check(lib().heatkv_rank_dispersion(shape.ref, betas.ctypes.data_as(C.POINTER(C.c_float)), int(betas.shape[0]),
                                         int(sinks), int(variant), out.ctypes.data_as(C.POINTER(C.c_double))))
     return out
+
+
+def heatkv_probe_tile_step_bytes():
+    return int(lib().heatkv_probe_tile_step_bytes())
+
+
+def heatkv_probe_tile_step(tiles, out, workgroups, iters, stream=None):
+    """Measurement aid: a model of the bf16 attention kernel's tile step (see include/heatkv.h)."""
+    _check_tensor(tiles, "tiles", min_bytes=heatkv_probe_tile_step_bytes())
+    _check_tensor(out, "out", min_bytes=max(int(workgroups), 0) * 256 * 4)
+    _check(lib().heatkv_probe_tile_step(_ptr(tiles), _ptr(out), int(workgroups), int(iters),
+                                        _stream() if stream is None else stream))

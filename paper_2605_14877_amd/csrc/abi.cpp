@@ -425,4 +425,15 @@ int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iter
   return HEATKV_OK;
 }
 
+size_t heatkv_probe_tile_step_bytes(void) { return heatkv::probe_tile_step_bytes(); }
+
+int heatkv_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, void* stream) {
+  if (!tiles || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
+  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || (iters & 1))
+    return fail(HEATKV_EINVAL, "probe size out of range (iters must be even)");
+  hipError_t e = heatkv::launch_probe_tile_step(tiles, out, workgroups, iters, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "probe_tile_step launch");
+  return HEATKV_OK;
+}
+
 }  // extern "C"

@@ -67,5 +67,9 @@ hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, co
 // operands taken from `operands` (probe_mfma_operand_bytes() bytes); out receives workgroups x 256 floats.
 size_t probe_mfma_operand_bytes();
 hipError_t launch_probe_mfma(const void* operands, float* out, int workgroups, int iters, hipStream_t stream);
+// Tile-step model of the bf16 attention kernel: `workgroups` x 4 wavefronts each run `iters` (even) model steps of
+// 32 MFMAs on the probe_tile_step_bytes() bytes of bf16 tile data in `tiles`; out receives workgroups x 256 floats.
+size_t probe_tile_step_bytes();
+hipError_t launch_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, hipStream_t stream);
 
 }  // namespace heatkv

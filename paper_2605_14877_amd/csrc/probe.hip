@@ -2,6 +2,8 @@
 // calibration kernels are priced against the datasheet peak; this loop of back-to-back, independent
 // v_mfma_f32_32x32x16_bf16 instructions (no memory traffic, no vector ALU work) shows what the same matrix
 // pipes deliver on the machine at hand, which depends on the operand data through the power-limited clock.
+#include <type_traits>
+
 #include "device_util.h"
 #include "kernels.h"
 
@@ -42,7 +44,161 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint4* ops, float
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// ---------------------------------------------------------------------------
+// Tile-step model: the instruction mix, dependencies and memory traffic of one step of the bf16 attention
+// kernel (per wavefront and 64-key tile: 16 score MFMAs fed from an LDS K tile, 32 scale FMAs, 32 exp2, 16
+// packs, 16 pair sums, 16 PV MFMAs fed from an LDS V tile through transposing reads, a 32-value max chain,
+// one barrier, and the HBM/L2 -> LDS copies of the next K and V tiles), without any of the kernel's
+// bookkeeping: no ragged tiles, no masks, no rescaling, every workgroup streams the same 2 MB of tiles (they
+// stay in L2).  Its throughput is what this mix sustains on the chip at hand; the numbers it computes mean
+// nothing.  Two workgroups of four wavefronts per compute unit, as in the kernel.
+// ---------------------------------------------------------------------------
+constexpr int kRowBytes = 256, kTileBytes = 64 * 256, kModelTiles = 64;
+
+__device__ __forceinline__ int model_swizzle_k(int row) { return row & 15; }
+__device__ __forceinline__ int model_swizzle_v(int row) { return (row & 3) << 2; }
+
+__global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv, float* out, int iters) {
+  __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, hl = lane >> 5;
+  for (int i = tid; i < 4 * kTileBytes / 4; i += 256)
+    reinterpret_cast<unsigned*>(&lds[0][0][0])[i] = reinterpret_cast<const unsigned*>(kv)[i];
+  __syncthreads();
+  union U {
+    uint4 u;
+    bf16x8 v;
+  };
+  bf16x8 qreg[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    U t;
+    t.u = reinterpret_cast<const uint4*>(kv)[(lane * 8 + i) & 1023];
+    qreg[i] = t.v;
+  }
+  int k_off[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * kRowBytes + (((2 * ks + hl) ^ model_swizzle_k(n)) << 4);
+  const int tr_i = lane & 15, tr_grp = lane >> 4;
+  const int v_row = 4 * hl + (tr_i >> 2);
+  int v_off[4];
+#pragma unroll
+  for (int dblk = 0; dblk < 4; ++dblk) {
+    const int chunk = 4 * dblk + 2 * (tr_grp & 1) + ((tr_i & 3) >> 1);
+    v_off[dblk] = v_row * kRowBytes + ((chunk ^ model_swizzle_v(v_row)) << 4) + ((tr_i & 1) << 3);
+  }
+  const int ld_row0 = 4 * wave + (lane >> 4);
+  const int ld_off_k = ld_row0 * kRowBytes + (((lane & 15) ^ model_swizzle_k(ld_row0)) << 4);
+  const int ld_off_v = ld_row0 * kRowBytes + (((lane & 15) ^ model_swizzle_v(ld_row0)) << 4);
+  const unsigned lds_base = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(
+      reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0][0][0]))));
+  // Copy of model tile `tile` (K: which = 0, V: which = 1) into buffer `buf`; all addresses stay inside the
+  // 2 * kModelTiles tiles of `kv` and inside the 64 KB of LDS.
+  auto issue = [&](int tile, int buf, int which) {
+    const char* src = kv + (which * kModelTiles + (tile & (kModelTiles - 1))) * kTileBytes;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const unsigned dst = lds_base + buf * (2 * kTileBytes) + which * kTileBytes + (4 * j + wave) * 1024;
+      const char* sj = src + j * 4096;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(which ? ld_off_v : ld_off_k), "s"(sj)
+                   : "memory");
+    }
+  };
+  f32x16 o[4], s_cur[2], s_nxt[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s_cur[i][r] = static_cast<float>(qreg[i][r & 7]);
+      s_nxt[i][r] = 0.f;
+    }
+  float l_run = 0.f, m_run = 0.f;
+  const float c = 0.1f;
+  const bf16x2 ones = {static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)};
+  union PB {
+    bf16x8 v;
+    bf16x2 h[4];
+  };
+  union VOperand {
+    struct {
+      s16x4 lo, hi;
+    } s;
+    bf16x8 v;
+  };
+  auto step = [&](int it, auto buf_tag) {
+    constexpr int buf = decltype(buf_tag)::value;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    issue(it + 2, buf, 0);
+    issue(it + 1, buf ^ 1, 1);
+    const char* kt = lds[buf ^ 1][0];
+    const char* vt = lds[buf][1];
+    const float mc = m_run * c;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_nxt[cb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * kRowBytes + k_off[ks]);
+        s_nxt[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s_nxt[cb], 0, 0, 0);
+      }
+#pragma unroll
+    for (int chunk = 0; chunk < 4; ++chunk) {
+      const int cb = chunk >> 1, ks = chunk & 1;
+      VOperand va[4];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const char* base = vt + 16 * chunk * kRowBytes + v_off[d];
+        va[d].s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
+        va[d].s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * kRowBytes));
+      }
+      PB pb;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pb.v[j] = static_cast<bf16_t>(fast_exp2(fmaf(s_cur[cb][8 * ks + j], c, -mc)));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) l_run = __builtin_amdgcn_fdot2_f32_bf16(pb.h[j], ones, l_run, false);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[d].v, pb.v, o[d], 0, 0, 0);
+    }
+    float mx = s_nxt[0][0];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_nxt[cb][r]);
+    m_run = fmaxf(m_run, mx * 1e-6f);
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) s_cur[cb] = s_nxt[cb];
+  };
+  for (int it = 0; it < iters; it += 2) {
+    step(it, std::integral_constant<int, 0>{});
+    step(it + 1, std::integral_constant<int, 1>{});
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  float acc = l_run + m_run;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc += o[i][r];
+  out[blockIdx.x * 256 + tid] = acc;
+}
+
 }  // namespace
+
+size_t probe_tile_step_bytes() { return size_t(2) * kModelTiles * kTileBytes; }
+
+hipError_t launch_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, hipStream_t stream) {
+  hipLaunchKernelGGL(probe_tile_step_kernel, dim3(workgroups), dim3(256), 0, stream, static_cast<const char*>(tiles), out,
+                     iters);
+  return hipGetLastError();
+}
 
 size_t probe_mfma_operand_bytes() { return size_t(kProbeOperands) * 16; }
 

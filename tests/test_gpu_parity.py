@@ -386,3 +386,19 @@ def test_bf16_calibrate_rising_and_falling_logits():
         for h in range(H):
             want = orc.beta_row(q[0, h].double().numpy(), k[0, h].double().numpy(), t1, k1 + 1, sm)[1:]
             assert np.abs(got[0, h] - want).max() <= 1e-4, (k1, h, np.abs(got[0, h] - want).max())
+
+
+def test_tile_step_probe_runs_and_is_deterministic():
+    n = hk.heatkv_probe_tile_step_bytes() // 2
+    g = torch.Generator(device="cuda").manual_seed(4)
+    tiles = torch.randn(n, device="cuda", generator=g).to(torch.bfloat16)
+    out1 = torch.empty(6 * 256, device="cuda")
+    out2 = torch.empty(6 * 256, device="cuda")
+    hk.heatkv_probe_tile_step(tiles, out1, 6, 4)
+    hk.heatkv_probe_tile_step(tiles, out2, 6, 4)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2)
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_probe_tile_step(tiles, out1, 6, 3)  # odd step count
+    with pytest.raises(ValueError):
+        hk.heatkv_probe_tile_step(tiles[:100], out1, 6, 4)
