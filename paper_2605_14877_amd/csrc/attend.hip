@@ -346,17 +346,27 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
 
   const float l_tot = sum_halves(l_run);
   const float inv = 1.f / l_tot;
-  if (q_row < t_k) {
-    bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(q_row) * D128;
+  // Output through LDS.  A lane owns one query row but only 4 consecutive columns at a time, so direct stores
+  // would be 8-byte pieces scattered over 32 rows.  The K buffers are idle by now (their last reader passed the
+  // barrier above and no copy is in flight), so every wavefront stages its 32 x 128 tile in 8 KB of them, with
+  // the 16-byte chunks XORed with the row number, and writes it out as whole 256-byte rows, 1 KB per instruction.
+  char* stage = lds[wave >> 1][0] + (wave & 1) * 8192;
 #pragma unroll
-    for (int dblk = 0; dblk < 4; ++dblk)
+  for (int dblk = 0; dblk < 4; ++dblk)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 v;
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + dblk * 32 + 8 * g + 4 * hl) = v;
-      }
+      for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
+      *reinterpret_cast<bf16x4*>(stage + n * ROW_BYTES + (((4 * dblk + g) ^ (n & 15)) << 4) + 8 * hl) = v;
+    }
+  const int out_row0 = qt * BM + wave * 32;
+  bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(out_row0) * D128;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int row = 4 * r + (lane >> 4), slot = lane & 15;
+    const uint4 v = *reinterpret_cast<const uint4*>(stage + row * ROW_BYTES + ((slot ^ (row & 15)) << 4));
+    if (out_row0 + row < t_k) *reinterpret_cast<uint4*>(op + row * D128 + slot * 8) = v;
   }
 }
 
