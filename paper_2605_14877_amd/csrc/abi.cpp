@@ -37,9 +37,9 @@ int ensure_uploaded(heatkv_plan* p) {
   if (p->dev.device == dev) return HEATKV_OK;
   if (p->dev.device >= 0) return fail(HEATKV_EINVAL, "plan was uploaded to another device");
   auto pad = [](size_t n) { return (n + 15) / 16 * 16; };
-  const size_t n3 = p->run_row.size() * sizeof(int32_t);
+  const size_t nw = p->run_row.size() * sizeof(heatkv::HeadWork);
   const size_t nd = p->descs.size() * sizeof(heatkv::CopyDesc);
-  const size_t o_row = 0, o_len = o_row + pad(n3), o_ord = o_len + pad(n3), o_desc = o_ord + pad(n3);
+  const size_t o_work = 0, o_desc = o_work + pad(nw);
   const size_t total = o_desc + pad(nd) + 16;
   std::vector<unsigned char> host;
   try {
@@ -47,9 +47,15 @@ int ensure_uploaded(heatkv_plan* p) {
   } catch (const std::bad_alloc&) {
     return fail(HEATKV_ENOMEM, "out of host memory");
   }
-  std::memcpy(host.data() + o_row, p->run_row.data(), n3);
-  std::memcpy(host.data() + o_len, p->run_len.data(), n3);
-  std::memcpy(host.data() + o_ord, p->head_order.data(), n3);
+  {  // per (scale, layer): the heads in the order of head_order, each with its run
+    heatkv::HeadWork* w = reinterpret_cast<heatkv::HeadWork*>(host.data() + o_work);
+    const size_t groups = p->run_row.size() / size_t(p->H);
+    for (size_t g = 0; g < groups; ++g)
+      for (int r = 0; r < p->H; ++r) {
+        const int32_t h = p->head_order[g * p->H + r];
+        w[g * p->H + r] = heatkv::HeadWork{h, p->run_row[g * p->H + h], p->run_len[g * p->H + h], 0};
+      }
+  }
   if (nd) std::memcpy(host.data() + o_desc, p->descs.data(), nd);
   void* block = nullptr;
   e = hipMalloc(&block, total);
@@ -61,9 +67,7 @@ int ensure_uploaded(heatkv_plan* p) {
   }
   unsigned char* base = static_cast<unsigned char*>(block);
   p->dev.block = block;
-  p->dev.run_row = reinterpret_cast<int32_t*>(base + o_row);
-  p->dev.run_len = reinterpret_cast<int32_t*>(base + o_len);
-  p->dev.head_order = reinterpret_cast<int32_t*>(base + o_ord);
+  p->dev.work = reinterpret_cast<heatkv::HeadWork*>(base + o_work);
   p->dev.descs = reinterpret_cast<heatkv::CopyDesc*>(base + o_desc);
   p->dev.device = dev;
   return HEATKV_OK;
@@ -288,9 +292,7 @@ int attend_impl(heatkv_plan* plan, int layer, int k, const void* q, const void* 
   a.t_k = plan->t[k];
   a.arena_tokens = plan->arena_tokens;
   const size_t off = plan->idx(k, layer, 0);
-  a.run_row = plan->dev.run_row + off;
-  a.run_len = plan->dev.run_len + off;
-  a.head_order = plan->dev.head_order + off;
+  a.work = plan->dev.work + off;
   a.max_len = max_len;
   a.q = q;
   a.k_cur = k_cur;

@@ -20,9 +20,7 @@ namespace {
 struct AttendParams {
   int H, batch, t_k;
   long long arena_tokens;
-  const int32_t* run_row;
-  const int32_t* run_len;
-  const int32_t* head_order;
+  const HeadWork* work;
   const void *q, *k_cur, *v_cur, *k_arena, *v_arena;
   void* out;
   float sm_scale;
@@ -98,12 +96,13 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   if (pair >= p.H * p.batch) return;
   const int qt = slot % p.n_qtiles;
   const int b = pair % p.batch;
-  const int h = p.head_order[pair / p.batch];
+  const HeadWork hw = p.work[pair / p.batch];  // one 16-byte record: head, first row and length of its run
+  const int h = hw.head;
 
   const int t_k = p.t_k;
-  const int n_prior = p.run_len[h];
+  const int n_prior = hw.run_len;
   const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D128;
-  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + p.run_row[h]) * D128;
+  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + hw.run_row) * D128;
   const char* k_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_arena) + run_off);
   const char* v_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_arena) + run_off);
   const char* k_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_cur) + cur_off);
@@ -394,13 +393,14 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(AttendParams p) {
   const int qt = id % p.n_qtiles;
   id /= p.n_qtiles;
   const int b = id % p.batch;
-  const int h = p.head_order[id / p.batch];
+  const HeadWork hw = p.work[id / p.batch];
+  const int h = hw.head;
 
   const int t_k = p.t_k;
-  const int n_prior = p.run_len[h];
+  const int n_prior = hw.run_len;
   const int n_total = n_prior + t_k;
   const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D;
-  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + p.run_row[h]) * D;
+  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + hw.run_row) * D;
   const float* k_prior = static_cast<const float*>(p.k_arena) + run_off;
   const float* v_prior = static_cast<const float*>(p.v_arena) + run_off;
   const float* k_cur = static_cast<const float*>(p.k_cur) + cur_off;
@@ -486,9 +486,7 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   p.batch = a.batch;
   p.t_k = a.t_k;
   p.arena_tokens = a.arena_tokens;
-  p.run_row = a.run_row;
-  p.run_len = a.run_len;
-  p.head_order = a.head_order;
+  p.work = a.work;
   p.q = a.q;
   p.k_cur = a.k_cur;
   p.v_cur = a.v_cur;

@@ -14,9 +14,7 @@ struct AttendArgs {
   int dtype, d, H, batch;
   int t_k;                   // queries (= current-scale keys) per head
   int64_t arena_tokens;      // rows per batch entry of each arena
-  const int32_t* run_row;    // device [H]
-  const int32_t* run_len;    // device [H]
-  const int32_t* head_order; // device [H]
+  const HeadWork* work;      // device [H]: the layer's heads by descending run length, each with its run
   int max_len;               // longest run among the H heads (host copy)
   const void *q, *k_cur, *v_cur, *k_arena, *v_arena;
   void* out;

@@ -21,13 +21,20 @@ struct CopyDesc {
   int32_t src_kind;
 };
 
+// What an attention workgroup needs to know about its head, one 16-byte record per (scale, layer, rank):
+// rank 0 is the head with the longest retained run (workgroups are dealt out longest first).
+struct HeadWork {
+  int32_t head;     // head index within the layer
+  int32_t run_row;  // first arena row of the head's run (per batch entry)
+  int32_t run_len;  // retained prior tokens
+  int32_t pad;
+};
+
 struct DeviceTables {
   int device = -1;
-  void* block = nullptr;          // one allocation holding the four tables below
-  int32_t* run_row = nullptr;     // [K][L][H] first arena row of the head's run
-  int32_t* run_len = nullptr;     // [K][L][H] retained prior tokens
-  int32_t* head_order = nullptr;  // [K][L][H] heads by descending run length
-  CopyDesc* descs = nullptr;      // all append descriptors, back to back
+  void* block = nullptr;      // one allocation holding the two tables below
+  HeadWork* work = nullptr;   // [K][L][H], by rank
+  CopyDesc* descs = nullptr;  // all append descriptors, back to back
 };
 
 }  // namespace heatkv
