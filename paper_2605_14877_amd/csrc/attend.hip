@@ -121,6 +121,13 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Tile schedule: tiles [0, tiles_cur) cover the current scale, the rest the retained run.
   const int tiles_cur = (t_k + BN - 1) / BN;
   const int tiles_all = tiles_cur + (n_prior + BN - 1) / BN;
+  // The query tiles of a (batch row, head) pair sit on one XCD, start together and walk at the same pace: walking
+  // in the same order they would all wait for the first touch of every tile (the requests merge, the wait does
+  // not).  Attention does not depend on the key order, so odd query tiles walk the tiles from the far end: each
+  // half of the walk is then fetched from HBM by one group and found in L2 by the other.  Scales of one or two
+  // query tiles keep the forward order (no gain measured there).
+  const bool walk_back = (qt & 1) && t_k > 2 * BM;
+  auto tile_of = [&](int step) { return walk_back ? tiles_all - 1 - step : step; };
 
   // Loader: wavefront w fills LDS bytes [(4j + w) KB, +1 KB) of a tile with instruction j = 0..3, lane L
   // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16 = ld_row0 + 16 j, slot L % 16.  The
@@ -169,7 +176,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Step `it` computes the scores of tile it+1 (matrix cores) while it turns the scores of tile `it` into
   // probabilities (vector ALU) and accumulates P V for tile `it`.  K tiles are therefore fetched one tile
   // further ahead than V tiles: at the top of step `it` the copies K(it+1) and V(it) must have landed.
-  auto issue_k = [&](int it, int buf) {
+  auto issue_k = [&](int step, int buf) {
+    const int it = tile_of(step);
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
@@ -188,7 +196,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(src) : "memory");
     }
   };
-  auto issue_v = [&](int it, int buf) {
+  auto issue_v = [&](int step, int buf) {
+    const int it = tile_of(step);
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
@@ -227,7 +236,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   };
   // Masks the ragged tail of tile `it`, folds its row maxima into the running reference and, rarely,
   // rescales what has been accumulated so far.
-  auto settle = [&](int it, f32x16 (&s)[2]) {
+  auto settle = [&](int step, f32x16 (&s)[2]) {
+    const int it = tile_of(step);
     const bool prior = it >= tiles_cur;
     const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
     if (left < BN) {
