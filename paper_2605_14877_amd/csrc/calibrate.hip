@@ -315,19 +315,31 @@ __global__ __launch_bounds__(256) void calibrate_f32_kernel(CalibParams p) {
   }
 }
 
+// Sum of one (batch row, head, key block) entry over the query tiles, in tile order, divided by the number of
+// query rows.  The loads of a group of eight go out together (the kernel is a chain of dependent additions fed
+// by L2 latency otherwise); the additions keep the order.
+__device__ __forceinline__ float tile_sum_in_order(const CalibParams& p, long long bh, int j) {
+  if (j > p.k1) return 0.f;
+  const float* src = p.partial + bh * p.n_qtiles * p.K + j;
+  float v = 0.f;
+  int qt = 0;
+  for (; qt + 8 <= p.n_qtiles; qt += 8) {
+    float x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = src[static_cast<long long>(qt + u) * p.K];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v += x[u];
+  }
+  for (; qt < p.n_qtiles; ++qt) v += src[static_cast<long long>(qt) * p.K];
+  return v / static_cast<float>(p.t_k1);
+}
+
 // Adds the per-tile partial sums in tile order and divides by the number of query rows.
 __global__ void calibrate_finish_kernel(CalibParams p) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   const int total = p.batch * p.H * p.K;
   if (i >= total) return;
-  const int j = i % p.K;
-  const long long bh = i / p.K;
-  float v = 0.f;
-  if (j <= p.k1) {
-    for (int qt = 0; qt < p.n_qtiles; ++qt) v += p.partial[(bh * p.n_qtiles + qt) * p.K + j];
-    v /= static_cast<float>(p.t_k1);
-  }
-  p.mass[i] = v;
+  p.mass[i] = tile_sum_in_order(p, i / p.K, i % p.K);
 }
 
 // Same reduction followed by the dataset average in one pass: one thread per (head, key block) walks the batch
@@ -339,11 +351,7 @@ __global__ void calibrate_finish_accumulate_kernel(CalibParams p) {
   float acc = 0.f;
   for (int b = 0; b < p.batch; ++b) {
     const long long bh = static_cast<long long>(b) * p.H + h;
-    float v = 0.f;
-    if (j <= p.k1) {
-      for (int qt = 0; qt < p.n_qtiles; ++qt) v += p.partial[(bh * p.n_qtiles + qt) * p.K + j];
-      v /= static_cast<float>(p.t_k1);
-    }
+    const float v = tile_sum_in_order(p, bh, j);
     if (p.mass) p.mass[bh * p.K + j] = v;
     acc += v;
   }
