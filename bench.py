@@ -46,6 +46,8 @@ def main():
                          "attend + append only (schedule from a fabricated beta table, no calibration pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend-only", action="store_true", help="profiling aid: skip calibrate/schedule in the step")
+    ap.add_argument("--calibrate-per-scale", action="store_true",
+                    help="calibrate with one call per scale instead of one launch for all scales")
     ap.add_argument("--separate-append", action="store_true",
                     help="call heatkv_attend_scale and heatkv_append_scale separately instead of the fused entry point")
     ap.add_argument("--graph", action="store_true",
@@ -103,15 +105,21 @@ def main():
 
     beta = torch.zeros(1, H, K, K, device=dev)
     mass = torch.empty(nb, H, K, device=dev)
-    cal_ws = [torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, i), 4), dtype=torch.uint8, device=dev)
-              for i in range(K)]
+    all_k1 = list(range(K))
+    cal_ws = torch.empty(hk.binding.calibrate_scales_workspace_bytes(shape, all_k1), dtype=torch.uint8, device=dev)
+    cal_ws_1 = [torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, i), 4), dtype=torch.uint8, device=dev)
+                for i in range(K)] if args.calibrate_per_scale else None
 
     def calibrate_and_plan():
         beta.zero_()
-        # the scales of a calibration pass are independent (each fills its own row of beta): largest first, so
-        # that the GPU is busy with the long kernels while the host enqueues the short ones
-        for k1 in reversed(range(K)):
-            hk.heatkv_calibrate_accumulate(shape, 0, k1, q_s[k1], kall_s[k1], sm, 1.0 / nb, beta, mass, cal_ws[k1])
+        # The scales of a calibration pass are independent (each fills its own row of beta) and the activations
+        # of all of them are recorded before the pass starts: one launch for all scales, one for the reduction.
+        if args.calibrate_per_scale:
+            for k1 in reversed(range(K)):
+                hk.heatkv_calibrate_accumulate(shape, 0, k1, q_s[k1], kall_s[k1], sm, 1.0 / nb, beta, mass,
+                                               cal_ws_1[k1])
+        else:
+            hk.heatkv_calibrate_scales_accumulate(shape, 0, all_k1, q_s, kall_s, sm, 1.0 / nb, beta, None, cal_ws)
         beta_h = beta.cpu().numpy()
         plan = hk.heatkv_build_schedule(shape, beta_h, budget_bytes, s)
         plan.upload()
@@ -204,7 +212,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: 1 layer x {H} heads x d{d} {cfg['dtype']}, batch {nb}, "
                                f"{K} scales ({c[-1]} tokens), {cfg['factor']}x budget, sinks {s}",
-                   "attend_only": bool(args.attend_only), "fused_append": not args.separate_append},
+                   "attend_only": bool(args.attend_only), "fused_append": not args.separate_append,
+                   "calibrate": "per scale" if args.calibrate_per_scale else "all scales in one launch"},
         "attend_scale_tflops": round(att_tflops, 2),
         "attend_scale_ms_per_step": round(total_att_ms, 4),
         "attend_pct_of_bf16_peak": round(100 * att_tflops / PEAK_BF16_TFLOPS, 2),

@@ -111,6 +111,20 @@ int heatkv_calibrate_accumulate(const heatkv_shape* shape, int layer, int k1, co
                                 float sm_scale, float weight, float* beta, float* mass, void* ws, size_t ws_bytes,
                                 void* stream);
 
+/* The same for several query scales in one launch (Sec. 3.1: the calibration set is processed offline, so the
+ * activations of all scales of a data point are available together, unlike during generation; one launch
+ * keeps the chip full where the short scales alone cannot).  Arithmetic and summation order per scale are
+ * those of heatkv_calibrate_accumulate, hence the same bits.
+ * n_scales  1..K; k1: host [n_scales], distinct scale indices in any order
+ * q, k_all  host arrays of n_scales device pointers, entry i laid out as for heatkv_calibrate with k1[i]
+ * mass      null, or a host array of n_scales device pointers (each fp32 [batch][H][K] or null)
+ * ws        device scratch of at least heatkv_calibrate_scales_workspace_bytes(shape, n_scales, k1) bytes
+ * The host arrays are read during the call only. */
+size_t heatkv_calibrate_scales_workspace_bytes(const heatkv_shape* shape, int n_scales, const int32_t* k1);
+int heatkv_calibrate_scales_accumulate(const heatkv_shape* shape, int layer, int n_scales, const int32_t* k1,
+                                       const void* const* q, const void* const* k_all, float sm_scale, float weight,
+                                       float* beta, float* const* mass, void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Schedule construction (Sec. 3.1 Eq. 3-4, Sec. 3.2 Eq. 5, Sec. 3.3 Alg. 1, App. A Alg. 2).
  * Host only, integer arithmetic except for the fp64 sums that rank the heads.

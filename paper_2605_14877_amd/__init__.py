@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     heatkv_build_schedule,
     heatkv_calibrate,
     heatkv_calibrate_accumulate,
+    heatkv_calibrate_scales_accumulate,
     heatkv_head_scores,
     heatkv_load_schedule,
     heatkv_probe_mfma,

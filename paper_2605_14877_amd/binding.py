@@ -58,6 +58,11 @@ def lib():
     L.heatkv_calibrate_accumulate.restype = C.c_int
     L.heatkv_calibrate_accumulate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, C.c_float, vp, vp, vp,
                                               C.c_size_t, vp]
+    L.heatkv_calibrate_scales_workspace_bytes.restype = C.c_size_t
+    L.heatkv_calibrate_scales_workspace_bytes.argtypes = [sp, C.c_int, i32p]
+    L.heatkv_calibrate_scales_accumulate.restype = C.c_int
+    L.heatkv_calibrate_scales_accumulate.argtypes = [sp, C.c_int, C.c_int, i32p, C.POINTER(vp), C.POINTER(vp),
+                                                     C.c_float, C.c_float, vp, C.POINTER(vp), vp, C.c_size_t, vp]
     L.heatkv_accumulate_beta.restype = C.c_int
     L.heatkv_accumulate_beta.argtypes = [sp, C.c_int, C.c_int, vp, C.c_float, vp, vp]
     L.heatkv_build_schedule.restype = C.c_int
@@ -337,6 +342,32 @@ def heatkv_calibrate_accumulate(shape, layer, k1, q, k_all, sm_scale, weight, be
     _check(lib().heatkv_calibrate_accumulate(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale),
                                              float(weight), _ptr(beta), _ptr(mass), _ptr(ws), ws_bytes,
                                              _stream() if stream is None else stream))
+
+
+def calibrate_scales_workspace_bytes(shape, k1_list):
+    k1 = (C.c_int32 * len(k1_list))(*[int(k) for k in k1_list])
+    return int(lib().heatkv_calibrate_scales_workspace_bytes(shape.ref, len(k1_list), k1))
+
+
+def heatkv_calibrate_scales_accumulate(shape, layer, k1_list, q_list, k_all_list, sm_scale, weight, beta, mass_list,
+                                       ws, stream=None):
+    """Eq. 2 masses of several query scales and their dataset average in one launch (see include/heatkv.h).
+    q_list / k_all_list: one tensor per entry of k1_list; mass_list: None or one tensor-or-None per entry."""
+    n = len(k1_list)
+    if len(q_list) != n or len(k_all_list) != n or (mass_list is not None and len(mass_list) != n):
+        raise ValueError("k1_list, q_list, k_all_list and mass_list must have the same length")
+    for i, k1 in enumerate(k1_list):
+        _check_calibrate_operands(shape, int(k1), q_list[i], k_all_list[i],
+                                  None if mass_list is None else mass_list[i], beta)
+    _check_tensor(ws, "ws")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    k1 = (C.c_int32 * n)(*[int(k) for k in k1_list])
+    qp = (C.c_void_p * n)(*[_ptr(x) for x in q_list])
+    kp = (C.c_void_p * n)(*[_ptr(x) for x in k_all_list])
+    mp = None if mass_list is None else (C.c_void_p * n)(*[_ptr(x) for x in mass_list])
+    _check(lib().heatkv_calibrate_scales_accumulate(shape.ref, layer, n, k1, qp, kp, float(sm_scale), float(weight),
+                                                    _ptr(beta), mp, _ptr(ws), ws_bytes,
+                                                    _stream() if stream is None else stream))
 
 
 def heatkv_probe_mfma_operand_bytes():

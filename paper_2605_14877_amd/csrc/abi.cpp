@@ -1,5 +1,6 @@
 // extern "C" entry points of libheatkv: argument checks, plan life cycle, and
 // the hand-off to the kernel launchers.  No arithmetic of the method lives here.
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <string>
@@ -339,30 +340,45 @@ size_t heatkv_calibrate_workspace_bytes(const heatkv_shape* shape, int k1) {
 
 namespace {
 
-int calibrate_impl(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all, float sm_scale,
-                   float* mass, float weight, float* beta, void* ws, size_t ws_bytes, void* stream) {
+int calibrate_impl(const heatkv_shape* shape, int layer, int n_scales, const int32_t* k1, const void* const* q,
+                   const void* const* k_all, float sm_scale, float* const* mass, float weight, float* beta, void* ws,
+                   size_t ws_bytes, void* stream) {
   int rc = heatkv::check_shape(shape);
   if (rc) return rc;
   if (layer < 0 || layer >= shape->L) return fail(HEATKV_EINVAL, "layer out of range");
-  if (k1 < 0 || k1 >= shape->K) return fail(HEATKV_EINVAL, "scale index out of range");
-  if (!q || !k_all || (!mass && !beta)) return fail(HEATKV_EINVAL, "null tensor pointer");
+  if (n_scales < 1 || n_scales > shape->K) return fail(HEATKV_EINVAL, "number of scales out of range");
+  if (!k1 || !q || !k_all) return fail(HEATKV_EINVAL, "null argument array");
   if (shape->dtype == HEATKV_BF16 && shape->d != 128)
     return fail(HEATKV_EINVAL, "bf16 calibration supports head dimension 128 only");
-  const size_t need =
-      heatkv::calibrate_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K, shape->t[k1]);
-  if (!ws || ws_bytes < need) return fail(HEATKV_EINVAL, "calibrate workspace too small");
   heatkv::CalibrateArgs a{};
+  bool seen[HEATKV_MAX_SCALES] = {};
+  for (int i = 0; i < n_scales; ++i) {
+    if (k1[i] < 0 || k1[i] >= shape->K) return fail(HEATKV_EINVAL, "scale index out of range");
+    if (seen[k1[i]]) return fail(HEATKV_EINVAL, "scale listed twice");
+    seen[k1[i]] = true;
+    float* m = mass ? mass[i] : nullptr;
+    if (!q[i] || !k_all[i] || (!m && !beta)) return fail(HEATKV_EINVAL, "null tensor pointer");
+    a.k1[i] = k1[i];
+    a.q[i] = q[i];
+    a.k_all[i] = k_all[i];
+    a.mass[i] = m;
+  }
+  const size_t need = heatkv::calibrate_scales_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K,
+                                                               shape->t, n_scales, k1);
+  // a single scale needs no padding between scales: the exact size is enough there
+  const size_t need_single =
+      heatkv::calibrate_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K, shape->t[k1[0]]);
+  if (!ws || ws_bytes < (n_scales == 1 ? need_single : need))
+    return fail(HEATKV_EINVAL, "calibrate workspace too small");
+  if (reinterpret_cast<uintptr_t>(ws) % 4 != 0) return fail(HEATKV_EINVAL, "calibrate workspace must be 4-byte aligned");
   a.dtype = shape->dtype;
   a.d = shape->d;
   a.H = shape->H;
   a.batch = shape->batch;
   a.K = shape->K;
-  a.k1 = k1;
+  a.n_scales = n_scales;
   for (int k = 0; k < shape->K; ++k) a.t[k] = shape->t[k];
-  a.q = q;
-  a.k_all = k_all;
   a.sm_scale = sm_scale;
-  a.mass = mass;
   a.ws = ws;
   a.beta = beta;
   a.weight = weight;
@@ -377,14 +393,31 @@ int calibrate_impl(const heatkv_shape* shape, int layer, int k1, const void* q, 
 int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all, float sm_scale,
                      float* mass, void* ws, size_t ws_bytes, void* stream) {
   if (!mass) return fail(HEATKV_EINVAL, "null tensor pointer");
-  return calibrate_impl(shape, layer, k1, q, k_all, sm_scale, mass, 0.f, nullptr, ws, ws_bytes, stream);
+  const int32_t k = k1;
+  return calibrate_impl(shape, layer, 1, &k, &q, &k_all, sm_scale, &mass, 0.f, nullptr, ws, ws_bytes, stream);
 }
 
 int heatkv_calibrate_accumulate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
                                 float sm_scale, float weight, float* beta, float* mass, void* ws, size_t ws_bytes,
                                 void* stream) {
   if (!beta) return fail(HEATKV_EINVAL, "null tensor pointer");
-  return calibrate_impl(shape, layer, k1, q, k_all, sm_scale, mass, weight, beta, ws, ws_bytes, stream);
+  const int32_t k = k1;
+  return calibrate_impl(shape, layer, 1, &k, &q, &k_all, sm_scale, &mass, weight, beta, ws, ws_bytes, stream);
+}
+
+size_t heatkv_calibrate_scales_workspace_bytes(const heatkv_shape* shape, int n_scales, const int32_t* k1) {
+  if (heatkv::check_shape(shape) || !k1 || n_scales < 1 || n_scales > shape->K) return 0;
+  for (int i = 0; i < n_scales; ++i)
+    if (k1[i] < 0 || k1[i] >= shape->K) return 0;
+  return heatkv::calibrate_scales_workspace_bytes(shape->dtype, shape->d, shape->H, shape->batch, shape->K, shape->t,
+                                                  n_scales, k1);
+}
+
+int heatkv_calibrate_scales_accumulate(const heatkv_shape* shape, int layer, int n_scales, const int32_t* k1,
+                                       const void* const* q, const void* const* k_all, float sm_scale, float weight,
+                                       float* beta, float* const* mass, void* ws, size_t ws_bytes, void* stream) {
+  if (!beta) return fail(HEATKV_EINVAL, "null tensor pointer");
+  return calibrate_impl(shape, layer, n_scales, k1, q, k_all, sm_scale, mass, weight, beta, ws, ws_bytes, stream);
 }
 
 int heatkv_accumulate_beta(const heatkv_shape* shape, int layer, int k1, const float* mass, float weight, float* beta,

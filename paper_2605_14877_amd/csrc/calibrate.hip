@@ -11,6 +11,7 @@
 // summed over the workgroup's rows in a fixed order and written as one partial
 // per (head, query tile); a second kernel adds the partials in tile order, so
 // the result is bit-reproducible (no floating-point atomics anywhere).
+#include <algorithm>
 #include <type_traits>
 
 #include "device_util.h"
@@ -22,18 +23,33 @@ namespace {
 
 constexpr int MAXK = HEATKV_MAX_SCALES;
 
-struct CalibParams {
-  int H, batch, K, k1, t_k1, n_qtiles;
-  int t[MAXK];
-  int c[MAXK];  // c[k] = t[0] + .. + t[k]
+// One query scale of a launch.  A launch may cover several (calibration data of all scales is available at
+// once, unlike generation); their workgroups are laid out one scale after the other, largest scale first.
+struct ScaleJob {
+  int k1;
+  int block_begin;  // first workgroup id of this scale (a multiple of 8 in the bf16 kernel)
   const void *q, *k_all;
-  float sm_scale;
   float* partial;  // [batch*H][n_qtiles][K]
   float* mass;     // [batch*H][K], may be null in the accumulating variant
-  float* beta;     // [L][H][K][K] or null
+};
+
+struct CalibParams {
+  int H, batch, K, n_scales;
+  int t[MAXK];
+  int c[MAXK];  // c[k] = t[0] + .. + t[k]
+  ScaleJob job[MAXK];
+  float sm_scale;
+  float* beta;  // [L][H][K][K] or null
   float weight;
   int layer;
 };
+
+// The scale a workgroup belongs to (workgroup-uniform, a handful of scalar compares).
+__device__ __forceinline__ int scale_of_block(const CalibParams& p, int block) {
+  int si = 0;
+  while (si + 1 < p.n_scales && block >= p.job[si + 1].block_begin) ++si;
+  return si;
+}
 
 // ---------------------------------------------------------------------------
 // bf16, d = 128: S^T = K Q^T on the matrix cores, one lane per query column
@@ -57,7 +73,10 @@ __host__ __device__ constexpr size_t calib_lds_bytes(int k1) {
 
 __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int k1 = p.k1, t_k1 = p.t_k1;
+  const ScaleJob& job = p.job[scale_of_block(p, blockIdx.x)];
+  const int k1 = job.k1, t_k1 = p.t[k1];
+  const int n_qtiles = (t_k1 + CBM - 1) / CBM;
+  const int block = blockIdx.x - job.block_begin;
   float* blk_sum = reinterpret_cast<float*>(lds + 2 * CTILE_BYTES);
   float* blk_max = blk_sum + (k1 + 1) * CBM;
   float* fin_max = blk_max + (k1 + 1) * CBM;
@@ -67,19 +86,19 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
   const int n = lane & 31, hl = lane >> 5;
 
   // All query tiles of one (batch row, head) read the same keys: give them ids on one XCD (id % 8).
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int bh = (slot / p.n_qtiles) * 8 + xcd;
+  const int xcd = block & 7, slot = block >> 3;  // block_begin is a multiple of 8: block & 7 is the hardware XCD
+  const int bh = (slot / n_qtiles) * 8 + xcd;
   if (bh >= p.batch * p.H) return;
-  const int qt = slot % p.n_qtiles;
+  const int qt = slot % n_qtiles;
   const int c_k1 = p.c[k1];
 
-  const char* kbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_all) +
+  const char* kbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(job.k_all) +
                                                     static_cast<long long>(bh) * c_k1 * CD);
   const int q_row = qt * CBM + wave * 32 + n;
   bf16x8 qreg[8];
   {
     const int ld = q_row < t_k1 ? q_row : t_k1 - 1;
-    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + (static_cast<long long>(bh) * t_k1 + ld) * CD + 8 * hl;
+    const bf16_t* qp = static_cast<const bf16_t*>(job.q) + (static_cast<long long>(bh) * t_k1 + ld) * CD + 8 * hl;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
@@ -228,7 +247,7 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
     float v = blk_sum[j * CBM + lane] + blk_sum[j * CBM + lane + 64];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    if (lane == 0) p.partial[(static_cast<long long>(bh) * p.n_qtiles + qt) * p.K + j] = v;
+    if (lane == 0) job.partial[(static_cast<long long>(bh) * n_qtiles + qt) * p.K + j] = v;
   }
 }
 
@@ -246,12 +265,14 @@ __global__ __launch_bounds__(256) void calibrate_f32_kernel(CalibParams p) {
   __shared__ float blk_max[MAXK][FQ];
 
   const int tid = threadIdx.x, r = tid >> 4, g = tid & 15;
-  int id = blockIdx.x;
-  const int qt = id % p.n_qtiles;
-  const int bh = id / p.n_qtiles;
-  const int t_k1 = p.t_k1, k1 = p.k1;
-  const float* kbase = static_cast<const float*>(p.k_all) + static_cast<long long>(bh) * p.c[k1] * D;
-  const float* q = static_cast<const float*>(p.q) + static_cast<long long>(bh) * t_k1 * D;
+  const ScaleJob& job = p.job[scale_of_block(p, blockIdx.x)];
+  const int k1 = job.k1, t_k1 = p.t[k1];
+  const int n_qtiles = (t_k1 + FQ - 1) / FQ;
+  const int id = blockIdx.x - job.block_begin;
+  const int qt = id % n_qtiles;
+  const int bh = id / n_qtiles;
+  const float* kbase = static_cast<const float*>(job.k_all) + static_cast<long long>(bh) * p.c[k1] * D;
+  const float* q = static_cast<const float*>(job.q) + static_cast<long long>(bh) * t_k1 * D;
 
   for (int e = tid; e < FQ * D; e += 256) {
     const int rr = e / D, dd = e % D;
@@ -311,51 +332,56 @@ __global__ __launch_bounds__(256) void calibrate_f32_kernel(CalibParams p) {
   if (tid <= k1) {
     float v = 0.f;
     for (int rr = 0; rr < FQ; ++rr) v += blk_sum[tid][rr];
-    p.partial[(static_cast<long long>(bh) * p.n_qtiles + qt) * p.K + tid] = v;
+    job.partial[(static_cast<long long>(bh) * n_qtiles + qt) * p.K + tid] = v;
   }
 }
 
 // Sum of one (batch row, head, key block) entry over the query tiles, in tile order, divided by the number of
 // query rows.  The loads of a group of eight go out together (the kernel is a chain of dependent additions fed
 // by L2 latency otherwise); the additions keep the order.
-__device__ __forceinline__ float tile_sum_in_order(const CalibParams& p, long long bh, int j) {
-  if (j > p.k1) return 0.f;
-  const float* src = p.partial + bh * p.n_qtiles * p.K + j;
+__device__ __forceinline__ float tile_sum_in_order(const CalibParams& p, const ScaleJob& job, int n_qtiles,
+                                                   long long bh, int j) {
+  if (j > job.k1) return 0.f;
+  const float* src = job.partial + bh * n_qtiles * p.K + j;
   float v = 0.f;
   int qt = 0;
-  for (; qt + 8 <= p.n_qtiles; qt += 8) {
+  for (; qt + 8 <= n_qtiles; qt += 8) {
     float x[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) x[u] = src[static_cast<long long>(qt + u) * p.K];
 #pragma unroll
     for (int u = 0; u < 8; ++u) v += x[u];
   }
-  for (; qt < p.n_qtiles; ++qt) v += src[static_cast<long long>(qt) * p.K];
-  return v / static_cast<float>(p.t_k1);
+  for (; qt < n_qtiles; ++qt) v += src[static_cast<long long>(qt) * p.K];
+  return v / static_cast<float>(p.t[job.k1]);
 }
 
-// Adds the per-tile partial sums in tile order and divides by the number of query rows.
-__global__ void calibrate_finish_kernel(CalibParams p) {
+// Adds the per-tile partial sums in tile order and divides by the number of query rows.  blockIdx.y = scale of
+// the launch; qpt = query rows per tile of the kernel that wrote the partials.
+__global__ void calibrate_finish_kernel(CalibParams p, int qpt) {
+  const ScaleJob& job = p.job[blockIdx.y];
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   const int total = p.batch * p.H * p.K;
   if (i >= total) return;
-  p.mass[i] = tile_sum_in_order(p, i / p.K, i % p.K);
+  job.mass[i] = tile_sum_in_order(p, job, (p.t[job.k1] + qpt - 1) / qpt, i / p.K, i % p.K);
 }
 
 // Same reduction followed by the dataset average in one pass: one thread per (head, key block) walks the batch
 // rows in order, so the result has the bits of calibrate_finish_kernel followed by accumulate_beta_kernel.
-__global__ void calibrate_finish_accumulate_kernel(CalibParams p) {
+__global__ void calibrate_finish_accumulate_kernel(CalibParams p, int qpt) {
+  const ScaleJob& job = p.job[blockIdx.y];
+  const int n_qtiles = (p.t[job.k1] + qpt - 1) / qpt;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= p.H * p.K) return;
   const int h = i / p.K, j = i % p.K;
   float acc = 0.f;
   for (int b = 0; b < p.batch; ++b) {
     const long long bh = static_cast<long long>(b) * p.H + h;
-    const float v = tile_sum_in_order(p, bh, j);
-    if (p.mass) p.mass[bh * p.K + j] = v;
+    const float v = tile_sum_in_order(p, job, n_qtiles, bh, j);
+    if (job.mass) job.mass[bh * p.K + j] = v;
     acc += v;
   }
-  p.beta[((static_cast<long long>(p.layer) * p.H + h) * p.K + p.k1) * p.K + j] += p.weight * acc;
+  p.beta[((static_cast<long long>(p.layer) * p.H + h) * p.K + job.k1) * p.K + j] += p.weight * acc;
 }
 
 __global__ void accumulate_beta_kernel(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
@@ -378,49 +404,72 @@ size_t calibrate_workspace_bytes(int dtype, int, int H, int batch, int K, int t_
   return size_t(batch) * H * n_qtiles * K * sizeof(float);
 }
 
+// Several scales in one launch: each scale's partials start on a 256-byte boundary.
+size_t calibrate_scales_workspace_bytes(int dtype, int d, int H, int batch, int K, const int32_t* t, int n_scales,
+                                        const int32_t* k1) {
+  size_t total = 0;
+  for (int i = 0; i < n_scales; ++i)
+    total += (calibrate_workspace_bytes(dtype, d, H, batch, K, t[k1[i]]) + 255) / 256 * 256;
+  return total;
+}
+
 hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
+  if (a.n_scales < 1 || a.n_scales > MAXK) return hipErrorInvalidValue;
   CalibParams p{};
   p.H = a.H;
   p.batch = a.batch;
   p.K = a.K;
-  p.k1 = a.k1;
-  p.t_k1 = a.t[a.k1];
+  p.n_scales = a.n_scales;
   int acc = 0;
   for (int k = 0; k < a.K; ++k) {
     p.t[k] = a.t[k];
     acc += a.t[k];
     p.c[k] = acc;
   }
-  const int qpt = queries_per_tile(a.dtype);
-  p.n_qtiles = (p.t_k1 + qpt - 1) / qpt;
-  p.q = a.q;
-  p.k_all = a.k_all;
   p.sm_scale = a.sm_scale;
-  p.partial = static_cast<float*>(a.ws);
-  p.mass = a.mass;
   p.beta = a.beta;
   p.weight = a.weight;
   p.layer = a.layer;
-  const unsigned grid = unsigned(p.n_qtiles) * a.H * a.batch;
-  if (a.dtype == HEATKV_BF16) {
-    if (a.d != 128) return hipErrorInvalidValue;
-    const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
-    hipLaunchKernelGGL(calibrate_bf16_d128_kernel, dim3(unsigned(p.n_qtiles) * pairs8), dim3(256),
-                       calib_lds_bytes(a.k1), stream, p);
-  } else if (a.d == 64) {
-    hipLaunchKernelGGL(calibrate_f32_kernel<64>, dim3(grid), dim3(256), 0, stream, p);
-  } else if (a.d == 128) {
-    hipLaunchKernelGGL(calibrate_f32_kernel<128>, dim3(grid), dim3(256), 0, stream, p);
-  } else {
-    return hipErrorInvalidValue;
+  const int qpt = queries_per_tile(a.dtype);
+  const bool mfma = a.dtype == HEATKV_BF16;
+  if (mfma && a.d != 128) return hipErrorInvalidValue;
+  if (!mfma && a.d != 64 && a.d != 128) return hipErrorInvalidValue;
+  // Largest scale first: its workgroups are the long ones, the short ones then fill the gaps they leave.
+  int order[MAXK];
+  for (int i = 0; i < a.n_scales; ++i) order[i] = i;
+  std::stable_sort(order, order + a.n_scales, [&](int x, int y) { return a.t[a.k1[x]] > a.t[a.k1[y]]; });
+  // In the bf16 kernel the (batch row, head) pairs are padded to a multiple of 8 so that id % 8 is the XCD.
+  const unsigned pairs = mfma ? (unsigned(a.H) * a.batch + 7) / 8 * 8 : unsigned(a.H) * a.batch;
+  unsigned blocks = 0;
+  size_t ws_off = 0;
+  int k1_max = 0;
+  for (int i = 0; i < a.n_scales; ++i) {
+    const int src = order[i];
+    ScaleJob& job = p.job[i];
+    job.k1 = a.k1[src];
+    job.block_begin = int(blocks);
+    job.q = a.q[src];
+    job.k_all = a.k_all[src];
+    job.partial = reinterpret_cast<float*>(static_cast<char*>(a.ws) + ws_off);
+    job.mass = a.mass[src];
+    blocks += unsigned((a.t[job.k1] + qpt - 1) / qpt) * pairs;
+    ws_off += (calibrate_workspace_bytes(a.dtype, a.d, a.H, a.batch, a.K, a.t[job.k1]) + 255) / 256 * 256;
+    k1_max = job.k1 > k1_max ? job.k1 : k1_max;
   }
+  if (mfma)
+    hipLaunchKernelGGL(calibrate_bf16_d128_kernel, dim3(blocks), dim3(256), calib_lds_bytes(k1_max), stream, p);
+  else if (a.d == 64)
+    hipLaunchKernelGGL(calibrate_f32_kernel<64>, dim3(blocks), dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL(calibrate_f32_kernel<128>, dim3(blocks), dim3(256), 0, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.beta) {
-    hipLaunchKernelGGL(calibrate_finish_accumulate_kernel, dim3((a.H * a.K + 255) / 256), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(calibrate_finish_accumulate_kernel, dim3((a.H * a.K + 255) / 256, a.n_scales), dim3(256), 0,
+                       stream, p, qpt);
   } else {
     const int total = a.batch * a.H * a.K;
-    hipLaunchKernelGGL(calibrate_finish_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(calibrate_finish_kernel, dim3((total + 255) / 256, a.n_scales), dim3(256), 0, stream, p, qpt);
   }
   return hipGetLastError();
 }

@@ -44,18 +44,25 @@ struct AppendArgs {
 hipError_t launch_append(const AppendArgs& a, hipStream_t stream);
 
 struct CalibrateArgs {
-  int dtype, d, H, batch, K, k1;
+  int dtype, d, H, batch, K;
   int32_t t[HEATKV_MAX_SCALES];
-  const void *q, *k_all;
+  // One launch covers n_scales query scales (distinct k1); entry i reads q[i] and k_all[i] and, if mass[i] is
+  // set, writes the per-row masses there.
+  int n_scales = 0;
+  int32_t k1[HEATKV_MAX_SCALES];
+  const void* q[HEATKV_MAX_SCALES];
+  const void* k_all[HEATKV_MAX_SCALES];
+  float* mass[HEATKV_MAX_SCALES];
   float sm_scale;
-  float* mass;
-  void* ws;
+  void* ws;  // calibrate_scales_workspace_bytes(...) bytes, 256-byte aligned
   // Optional fused dataset average: beta[layer][h][k1][:] += weight * sum_b mass[b][h][:] (mass may then be null).
   float* beta = nullptr;
   float weight = 0.f;
   int layer = 0;
 };
 size_t calibrate_workspace_bytes(int dtype, int d, int H, int batch, int K, int t_k1);
+size_t calibrate_scales_workspace_bytes(int dtype, int d, int H, int batch, int K, const int32_t* t, int n_scales,
+                                        const int32_t* k1);
 hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);
 // beta[(layer*H + h)*K*K + k1*K + k2] += weight * sum_b mass[(b*H + h)*K + k2]
 hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,

@@ -202,6 +202,39 @@ def test_error_codes():
     assert hk.heatkv_probe_mfma_operand_bytes() == 65536
 
 
+def test_calibrate_scales_argument_checks():
+    # everything that can be wrong with the scale list is rejected before any GPU call
+    import ctypes as C
+    from paper_2605_14877_amd import binding
+    L = binding.lib()
+    t0 = hi.tokens_per_scale(hi.SIDES_TINY)
+    shape = hk.Shape(1, 4, 64, t0, 1, "f32")
+    K = len(t0)
+    fake = (C.c_void_p * K)(*[0x1000] * K)  # never dereferenced by the calls below
+
+    def call(k1_list, ws_bytes, beta=0x1000, q=fake, k_all=fake):
+        k1 = (C.c_int32 * max(len(k1_list), 1))(*k1_list)
+        return L.heatkv_calibrate_scales_accumulate(shape.ref, 0, len(k1_list), k1, q, k_all, 0.125, 1.0, beta, None,
+                                                    0x1000, ws_bytes, None)
+
+    assert call([], 1 << 20) == -1                      # no scale
+    assert call([0, 1, 2, 3, 0], 1 << 20) == -1         # more scales than the shape has
+    assert call([0, 4], 1 << 20) == -1                  # index out of range
+    assert call([2, 1, 2], 1 << 20) == -1               # listed twice
+    assert b"twice" in L.heatkv_last_error()
+    assert call([1, 2], 1 << 20, beta=None) == -1       # no beta
+    assert call([1, 2], 1 << 20, q=None) == -1          # no pointer array
+    need = binding.calibrate_scales_workspace_bytes(shape, [3, 1, 2])
+    # per scale: batch*H * ceil(t/16) query tiles * K floats, rounded up to 256 bytes
+    want = sum((1 * 4 * -(-int(t0[k]) // 16) * K * 4 + 255) // 256 * 256 for k in (3, 1, 2))
+    assert need == want
+    assert call([3, 1, 2], need - 1) == -1              # workspace too small
+    assert b"workspace" in L.heatkv_last_error()
+    assert binding.calibrate_scales_workspace_bytes(shape, [0, 7]) == 0
+    with pytest.raises(ValueError, match="same length"):
+        hk.heatkv_calibrate_scales_accumulate(shape, 0, [1, 2], [None], [None, None], 0.125, 1.0, None, None, None)
+
+
 def test_full_budget_plan_keeps_everything():
     t0 = hi.tokens_per_scale(hi.SIDES_TINY)
     c = hi.cumulative_tokens(t0)

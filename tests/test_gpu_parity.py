@@ -388,6 +388,48 @@ def test_bf16_calibrate_rising_and_falling_logits():
             assert np.abs(got[0, h] - want).max() <= 1e-4, (k1, h, np.abs(got[0, h] - want).max())
 
 
+@pytest.mark.parametrize("dtype,d,sides", [("bf16", 128, (1, 2, 4, 8, 13, 20)), ("f32", 64, (1, 2, 4, 7, 9))])
+def test_calibrate_all_scales_in_one_launch_has_the_bits_of_the_per_scale_calls(dtype, d, sides):
+    # Calibration data of all scales is available at once, so the library can take them in one launch; masses
+    # and the accumulated beta must be bit-identical to the per-scale calls, for all scales and for a subset
+    # given in arbitrary order.
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K, H, batch = len(t0), 3, 2
+    sm = 1.0 / np.sqrt(d)
+    g = torch.Generator().manual_seed(41)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    q = torch.randn(batch, H, c[-1], d, generator=g).to(td)
+    k = torch.randn(batch, H, c[-1], d, generator=g).to(td)
+    dq, dk = _dev(q, k)
+    shape = hk.Shape(2, H, d, t0, batch, dtype)
+    qs = [dq[:, :, c[i] - t0[i]:c[i]].contiguous() for i in range(K)]
+    ks = [dk[:, :, :c[i]].contiguous() for i in range(K)]
+    for k1_list in (list(range(K)), [K - 2, 0, K - 1, 2]):
+        beta_a = torch.zeros(2, H, K, K, device="cuda")
+        mass_a = [torch.full((batch, H, K), -1.0, device="cuda") for _ in k1_list]
+        for i, k1 in enumerate(k1_list):
+            ws = torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device="cuda")
+            hk.heatkv_calibrate_accumulate(shape, 1, k1, qs[k1], ks[k1], sm, 0.25, beta_a, mass_a[i], ws)
+        beta_b = torch.zeros(2, H, K, K, device="cuda")
+        mass_b = [torch.full((batch, H, K), -2.0, device="cuda") for _ in k1_list]
+        mass_b[1] = None  # a scale whose per-row masses are not wanted
+        ws = torch.empty(hk.binding.calibrate_scales_workspace_bytes(shape, k1_list), dtype=torch.uint8, device="cuda")
+        hk.heatkv_calibrate_scales_accumulate(shape, 1, k1_list, [qs[i] for i in k1_list], [ks[i] for i in k1_list],
+                                              sm, 0.25, beta_b, mass_b, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(beta_a, beta_b)
+        assert float(beta_b[0].abs().max()) == 0.0 and float(beta_b[1].abs().max()) > 0.0
+        for i in range(len(k1_list)):
+            if mass_b[i] is not None:
+                assert torch.equal(mass_a[i], mass_b[i]), (k1_list, i)
+    # and against the oracle for one head of the largest scale
+    t1 = orc.one_based(t0)
+    want = orc.beta_row(q[0, 1].double().numpy(), k[0, 1].double().numpy(), t1, K, sm)[1:]
+    got = mass_a[2][0, 1].cpu().double().numpy()
+    assert np.abs(got - want).max() <= 1e-4
+
+
 def test_tile_step_probe_runs_and_is_deterministic():
     n = hk.heatkv_probe_tile_step_bytes() // 2
     g = torch.Generator(device="cuda").manual_seed(4)
