@@ -121,13 +121,6 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Tile schedule: tiles [0, tiles_cur) cover the current scale, the rest the retained run.
   const int tiles_cur = (t_k + BN - 1) / BN;
   const int tiles_all = tiles_cur + (n_prior + BN - 1) / BN;
-  // The query tiles of a (batch row, head) pair sit on one XCD, start together and walk at the same pace: walking
-  // in the same order they would all wait for the first touch of every tile (the requests merge, the wait does
-  // not).  Attention does not depend on the key order, so odd query tiles walk the tiles from the far end: each
-  // half of the walk is then fetched from HBM by one group and found in L2 by the other.  Scales of one or two
-  // query tiles keep the forward order (no gain measured there).
-  const bool walk_back = (qt & 1) && t_k > 2 * BM;
-  auto tile_of = [&](int step) { return walk_back ? tiles_all - 1 - step : step; };
 
   // Loader: wavefront w fills LDS bytes [(4j + w) KB, +1 KB) of a tile with instruction j = 0..3, lane L
   // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16 = ld_row0 + 16 j, slot L % 16.  The
@@ -176,44 +169,50 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Step `it` computes the scores of tile it+1 (matrix cores) while it turns the scores of tile `it` into
   // probabilities (vector ALU) and accumulates P V for tile `it`.  K tiles are therefore fetched one tile
   // further ahead than V tiles: at the top of step `it` the copies K(it+1) and V(it) must have landed.
-  auto issue_k = [&](int step, int buf) {
-    const int it = tile_of(step);
+  auto issue_k = [&](int it, int buf) {
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
     const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
+    const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + wave * 1024;
+    if (left >= BN) {  // workgroup-uniform; the full-tile path has no per-lane arithmetic at all
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int off = ld_off_k;
-      const char* src = kb + j * (16 * ROW_BYTES);
-      if (left < BN) {  // ragged tile: rows past the end re-read the last valid row
+      for (int j = 0; j < 4; ++j)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd + j * 4096), "v"(ld_off_k),
+                     "s"(kb + j * (16 * ROW_BYTES))
+                     : "memory");
+    } else {  // ragged tile: rows past the end re-read the last valid row
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
         const int row = ld_row0 + 16 * j;
         const int rr = row < left ? row : left - 1;
-        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_k(row)) << 4);
-        src = kb;
+        const int off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_k(row)) << 4);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t; ragged" ::"s"(kd + j * 4096), "v"(off), "s"(kb)
+                     : "memory");
       }
-      const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(src) : "memory");
     }
   };
-  auto issue_v = [&](int step, int buf) {
-    const int it = tile_of(step);
+  auto issue_v = [&](int it, int buf) {
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
+    const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES + wave * 1024;
+    if (left >= BN) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int off = ld_off_v;
-      const char* src = vb + j * (16 * ROW_BYTES);
-      if (left < BN) {
+      for (int j = 0; j < 4; ++j)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd + j * 4096), "v"(ld_off_v),
+                     "s"(vb + j * (16 * ROW_BYTES))
+                     : "memory");
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
         const int row = ld_row0 + 16 * j;
         const int rr = row < left ? row : left - 1;
-        off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_v(row)) << 4);
-        src = vb;
+        const int off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_v(row)) << 4);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t; ragged" ::"s"(vd + j * 4096), "v"(off), "s"(vb)
+                     : "memory");
       }
-      const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd), "v"(off), "s"(src) : "memory");
     }
   };
 
@@ -236,8 +235,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   };
   // Masks the ragged tail of tile `it`, folds its row maxima into the running reference and, rarely,
   // rescales what has been accumulated so far.
-  auto settle = [&](int step, f32x16 (&s)[2]) {
-    const int it = tile_of(step);
+  auto settle = [&](int it, f32x16 (&s)[2]) {
     const bool prior = it >= tiles_cur;
     const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
     if (left < BN) {
@@ -305,17 +303,17 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // every tile and keeps the barriers, but leaves the matrix cores to the other workgroup on the unit.
   const bool active = qt * BM + wave * 32 < t_k;
   // Steady-state step for tile `it` (it + 1 < tiles_all); K(it+1) sits in K buffer kb1, V(it) in V buffer vb0.
-  auto pipe_step = [&](int it, auto kb1, auto vb0) {
+  // s_in holds the scores of tile `it`, s_out receives those of tile it+1: the two register sets swap roles
+  // from step to step instead of being copied.
+  auto pipe_step = [&](int it, auto kb1, auto vb0, f32x16 (&s_in)[2], f32x16 (&s_out)[2]) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (it + 2 < tiles_all) issue_k(it + 2, decltype(vb0)::value);      // K buffer it & 1 was read by step it-1
     issue_v(it + 1, decltype(kb1)::value);                              // V buffer (it+1) & 1 likewise
     if (!active) return;
-    scores(s_nxt, kb1);
-    accumulate(s_cur, vb0);
-    settle(it + 1, s_nxt);
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) s_cur[cb] = s_nxt[cb];
+    scores(s_out, kb1);
+    accumulate(s_in, vb0);
+    settle(it + 1, s_out);
   };
 
   // Prologue: K(0), K(1) and V(0) all go out at once (one memory round trip instead of two before the loop,
@@ -336,12 +334,12 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
     settle(0, s_cur);
   }
   int it = 0;
-  for (; it + 2 < tiles_all; it += 2) {
-    pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
-    pipe_step(it + 1, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+  for (; it + 2 < tiles_all; it += 2) {  // scores of even tiles live in s_cur, of odd tiles in s_nxt
+    pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, s_cur, s_nxt);
+    pipe_step(it + 1, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, s_nxt, s_cur);
   }
   if (it + 1 < tiles_all) {
-    pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+    pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, s_cur, s_nxt);
     ++it;
   }
   // Epilogue: the last tile has scores but no successor.
@@ -349,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   __syncthreads();
   if (!active) return;
   if (it & 1)
-    accumulate(s_cur, std::integral_constant<int, 1>{});
+    accumulate(s_nxt, std::integral_constant<int, 1>{});
   else
     accumulate(s_cur, std::integral_constant<int, 0>{});
 
