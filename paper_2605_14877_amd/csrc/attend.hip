@@ -238,7 +238,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   auto settle = [&](int it, f32x16 (&s)[2]) {
     const bool prior = it >= tiles_cur;
     const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
-    if (left < BN) {
+    if (left < BN) {  // workgroup-uniform and rare: kept a branch (the empty asm keeps it from becoming 32 selects)
+      asm volatile("; ragged tile mask" ::: "memory");
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
