@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # HBM bytes per attend launch (average over the 13 launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
 # scaled by a plain copy of known size; see profiles/attend_layer2b_hbm_traffic.txt.  Other workloads: not measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"layer2b": 38.8e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"layer2b": 37.3e6}
 
 
 def main():
