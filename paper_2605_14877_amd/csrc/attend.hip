@@ -175,7 +175,10 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
     const int left = (prior ? n_prior : t_k) - local * BN;
     const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
     const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + wave * 1024;
-    if (left >= BN) {  // workgroup-uniform; the full-tile path has no per-lane arithmetic at all
+    // Two separate statements under a workgroup-uniform branch: the full-tile path has no per-lane arithmetic at
+    // all.  (The comment inside the ragged variant's text keeps the two from being merged back into one
+    // statement with per-lane selected operands, 24 vector instructions in every step.)
+    if (left >= BN) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd + j * 4096), "v"(ld_off_k),
