@@ -6,6 +6,7 @@
 // the current scale.  Both kernels walk this virtual key sequence in tiles,
 // keep running row maxima and row sums in fp32 (online softmax) and normalise
 // once at the end.
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -75,16 +76,31 @@ constexpr int TILE_BYTES = BN * ROW_BYTES;
 __device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
 __device__ __forceinline__ int swizzle_v(int row) { return (row & 3) << 2; }
 
-__global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds[2][2][TILE_BYTES];  // [buffer][K,V]
+extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 
-  if (static_cast<int>(blockIdx.x) >= p.attend_blocks) {  // fused append: a plain row copy
+// KS = number of key streams.  KS = 1: the workgroup described above.  KS = 2, for launches that give every
+// compute unit at most one workgroup (few heads, small batch): 8 wavefronts, one workgroup per unit; wavefronts
+// 4-7 take the same 128 queries as 0-3 but every other key tile (stream g walks tiles g, g + 2, ...), each
+// stream with its own pair of tile stages (128 KB of dynamic LDS), and at the end stream 1 hands its partial
+// output, row sums and references to stream 0 through LDS.  The unit then runs two wavefronts per SIMD, as it
+// does when two workgroups share it, without a second pass over HBM.
+template <int KS>
+__global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_kernel(AttendParams p) {
+  static_assert(KS == 1 || KS == 2, "one or two key streams");
+  __shared__ __attribute__((aligned(1024))) char lds_static[KS == 1 ? 2 : 1][2][KS == 1 ? TILE_BYTES : 16];
+  // [stream * 2 + stage][K,V]; 64 KB are static, 128 KB exceed the static limit and come as dynamic LDS
+  char(*lds)[2][TILE_BYTES] = KS == 1 ? reinterpret_cast<char(*)[2][TILE_BYTES]>(&lds_static[0][0][0])
+                                      : reinterpret_cast<char(*)[2][TILE_BYTES]>(attend_dynamic_lds);
+
+  if (static_cast<int>(blockIdx.x) >= p.attend_blocks) {  // fused append: a plain row copy by 256 lanes
     const int j = blockIdx.x - p.attend_blocks;
-    copy_rows_block(p.copy, j % p.ndesc, j / p.ndesc);
+    if (KS == 1 || threadIdx.x < 256) copy_rows_block(p.copy, j % p.ndesc, j / p.ndesc);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform, kept in a scalar register
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform, kept in a scalar register
+  const int g = KS == 1 ? 0 : wave_all >> 2;                      // key stream of this wavefront
+  const int wave = wave_all & 3;                                  // its place among the four of the stream
   const int n = lane & 31, hl = lane >> 5;
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All query tiles of one
@@ -121,6 +137,10 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Tile schedule: tiles [0, tiles_cur) cover the current scale, the rest the retained run.
   const int tiles_cur = (t_k + BN - 1) / BN;
   const int tiles_all = tiles_cur + (n_prior + BN - 1) / BN;
+  // Step j of stream g works on tile KS j + g; all streams make steps_all steps (the barriers are shared), a
+  // stream whose last step has no tile sits it out.
+  const int steps_all = (tiles_all + KS - 1) / KS;
+  auto has_tile = [&](int j) { return KS == 1 || KS * j + g < tiles_all; };
 
   // Loader: wavefront w fills LDS bytes [(4j + w) KB, +1 KB) of a tile with instruction j = 0..3, lane L
   // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16 = ld_row0 + 16 j, slot L % 16.  The
@@ -134,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // buffer (it would wait for the whole prefetch in the middle of the math).  Ordering is explicit
   // instead: s_waitcnt vmcnt(0) and the workgroup barrier at the top of every tile step.
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<unsigned long long>(
-      (__attribute__((address_space(3))) char*)(&lds[0][0][0])));
+      (__attribute__((address_space(3))) char*)(&lds[0][0][0]))) + g * (4 * TILE_BYTES);
   // Reader offsets inside a tile.
   int k_off[8];  // K operand: row n (+32 cb), chunk 2 ks + hl
 #pragma unroll
@@ -169,7 +189,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // Step `it` computes the scores of tile it+1 (matrix cores) while it turns the scores of tile `it` into
   // probabilities (vector ALU) and accumulates P V for tile `it`.  K tiles are therefore fetched one tile
   // further ahead than V tiles: at the top of step `it` the copies K(it+1) and V(it) must have landed.
-  auto issue_k = [&](int it, int buf) {
+  auto issue_k = [&](int j, int buf) {
+    const int it = KS * j + g;
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
@@ -195,7 +216,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
       }
     }
   };
-  auto issue_v = [&](int it, int buf) {
+  auto issue_v = [&](int j, int buf) {
+    const int it = KS * j + g;
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
@@ -223,7 +245,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // s[cb][r] is key 32*cb + 8*(r/4) + 4*hl + r%4 of the tile, query column n.
   auto scores = [&](f32x16 (&s)[2], auto buf_tag) {
     constexpr int buf = decltype(buf_tag)::value;
-    const char* kt = lds[buf][0];
+    const char* kt = lds[2 * g + buf][0];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -238,7 +260,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   };
   // Masks the ragged tail of tile `it`, folds its row maxima into the running reference and, rarely,
   // rescales what has been accumulated so far.
-  auto settle = [&](int it, f32x16 (&s)[2]) {
+  auto settle = [&](int j, f32x16 (&s)[2]) {
+    const int it = KS * j + g;
     const bool prior = it >= tiles_cur;
     const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
     if (left < BN) {  // workgroup-uniform and rare: kept a branch (the empty asm keeps it from becoming 32 selects)
@@ -276,7 +299,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   };
   auto accumulate = [&](const f32x16 (&s)[2], auto buf_tag) {
     constexpr int buf = decltype(buf_tag)::value;
-    const char* vt = lds[buf][1];
+    const char* vt = lds[2 * g + buf][1];
     const float mc = m_run * c;
 #pragma unroll
     for (int chunk = 0; chunk < 4; ++chunk) {
@@ -306,54 +329,88 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_d128_kernel(AttendParams p
   // A wavefront whose 32 query rows all lie past t_k (ragged last query tile) keeps loading its share of
   // every tile and keeps the barriers, but leaves the matrix cores to the other workgroup on the unit.
   const bool active = qt * BM + wave * 32 < t_k;
-  // Steady-state step for tile `it` (it + 1 < tiles_all); K(it+1) sits in K buffer kb1, V(it) in V buffer vb0.
-  // s_in holds the scores of tile `it`, s_out receives those of tile it+1: the two register sets swap roles
-  // from step to step instead of being copied.
-  auto pipe_step = [&](int it, auto kb1, auto vb0, f32x16 (&s_in)[2], f32x16 (&s_out)[2]) {
+  // Steady-state step j (j + 1 < steps_all): K of the stream's tile j+1 sits in K stage kb1, V of its tile j in
+  // V stage vb0.  s_in holds the scores of tile j, s_out receives those of tile j+1: the two register sets swap
+  // roles from step to step instead of being copied.
+  auto pipe_step = [&](int j, auto kb1, auto vb0, f32x16 (&s_in)[2], f32x16 (&s_out)[2]) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (it + 2 < tiles_all) issue_k(it + 2, decltype(vb0)::value);      // K buffer it & 1 was read by step it-1
-    issue_v(it + 1, decltype(kb1)::value);                              // V buffer (it+1) & 1 likewise
+    if (j + 2 < steps_all && has_tile(j + 2)) issue_k(j + 2, decltype(vb0)::value);  // K stage j & 1: read by step j-1
+    if (has_tile(j + 1)) issue_v(j + 1, decltype(kb1)::value);                       // V stage (j+1) & 1 likewise
     if (!active) return;
-    scores(s_out, kb1);
+    if (has_tile(j + 1)) scores(s_out, kb1);
     accumulate(s_in, vb0);
-    settle(it + 1, s_out);
+    if (has_tile(j + 1)) settle(j + 1, s_out);
   };
 
   // Prologue: K(0), K(1) and V(0) all go out at once (one memory round trip instead of two before the loop,
   // which is what the short scales are made of); loads return in issue order, so waiting until at most the
   // eight younger copies are outstanding means K(0) has landed.
-  issue_k(0, 0);
-  if (tiles_all > 1) {
-    issue_k(1, 1);
-    issue_v(0, 0);
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  } else {
-    issue_v(0, 0);
-    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if (KS == 1) {
+    issue_k(0, 0);
+    if (tiles_all > 1) {
+      issue_k(1, 1);
+      issue_v(0, 0);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    } else {
+      issue_v(0, 0);
+      asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    }
+  } else {  // a stream may have no tile at all, or one: everything it has goes out, then a full wait
+    if (has_tile(0)) issue_k(0, 0);
+    if (steps_all > 1 && has_tile(1)) issue_k(1, 1);
+    if (has_tile(0)) issue_v(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
   __syncthreads();
-  if (active) {
+  if (active && has_tile(0)) {
     scores(s_cur, std::integral_constant<int, 0>{});
     settle(0, s_cur);
   }
   int it = 0;
-  for (; it + 2 < tiles_all; it += 2) {  // scores of even tiles live in s_cur, of odd tiles in s_nxt
+  for (; it + 2 < steps_all; it += 2) {  // scores of even steps live in s_cur, of odd steps in s_nxt
     pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, s_cur, s_nxt);
     pipe_step(it + 1, std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, s_nxt, s_cur);
   }
-  if (it + 1 < tiles_all) {
+  if (it + 1 < steps_all) {
     pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, s_cur, s_nxt);
     ++it;
   }
   // Epilogue: the last tile has scores but no successor.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (!active) return;
-  if (it & 1)
-    accumulate(s_nxt, std::integral_constant<int, 1>{});
-  else
-    accumulate(s_cur, std::integral_constant<int, 0>{});
+  if (KS == 1 && !active) return;
+  if (active && has_tile(it)) {
+    if (it & 1)
+      accumulate(s_nxt, std::integral_constant<int, 1>{});
+    else
+      accumulate(s_cur, std::integral_constant<int, 0>{});
+  }
+  if constexpr (KS == 2) {
+    // Stream 1 parks its accumulators (64 registers, one 256-byte row of LDS per register), row-sum partials and
+    // references in the idle tile stages (66 KB from byte 48 K on: clear of the 16 KB at 0 and at 32 K where
+    // stream 0 stages its output); stream 0 brings both halves to the larger reference and adds.
+    __syncthreads();  // every wavefront has finished reading the tile stages
+    float* park = reinterpret_cast<float*>(lds[1][1]) + wave * (66 * 64);
+    if (g == 1 && active) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) park[(16 * i + r) * 64 + lane] = o[i][r];
+      park[64 * 64 + lane] = m_run;
+      park[65 * 64 + lane] = l_run;
+    }
+    __syncthreads();
+    if (g == 1 || !active) return;
+    const float m_other = park[64 * 64 + lane], l_other = park[65 * 64 + lane];
+    const float m_new = fmaxf(m_run, m_other);  // m_run is finite: stream 0 always has tile 0
+    const float a0 = fast_exp2((m_run - m_new) * c), a1 = fast_exp2((m_other - m_new) * c);  // 2^-inf = 0: no tile
+    l_run = l_run * a0 + l_other * a1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][r] = o[i][r] * a0 + park[(16 * i + r) * 64 + lane] * a1;
+  }
 
   const float l_tot = sum_halves(l_run);
   const float inv = 1.f / l_tot;
@@ -492,6 +549,27 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(AttendParams p) {
 
 size_t attend_workspace_bytes(int, int, int, int, int, int) { return 0; }
 
+namespace {
+
+constexpr int TWO_STREAM_LDS_BYTES = 2 * 2 * 2 * TILE_BYTES;  // two streams x two stages x (K, V)
+constexpr int TWO_STREAM_MAX_BLOCKS = 256;                    // compute units of the chip
+constexpr int TWO_STREAM_MIN_TOKENS = 384;                    // shorter walks gain nothing (measured at 256)
+
+// 128 KB of dynamic LDS need the function attribute raised, once per device.
+hipError_t allow_two_stream_lds() {
+  static std::atomic<unsigned long long> done{0};  // one bit per device ordinal below 64
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && (done.load(std::memory_order_acquire) >> dev & 1)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_d128_kernel<2>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, TWO_STREAM_LDS_BYTES);
+  if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
+  return e;
+}
+
+}  // namespace
+
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   AttendParams p{};
   p.H = a.H;
@@ -526,8 +604,15 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
     p.n_qtiles = (a.t_k + BM - 1) / BM;
     const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
     p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
-    hipLaunchKernelGGL(attend_bf16_d128_kernel, dim3(unsigned(p.attend_blocks) + copy_blocks), dim3(256), 0, stream,
-                       p);
+    const dim3 grid(unsigned(p.attend_blocks) + copy_blocks);
+    // At most one workgroup per compute unit: two key streams per workgroup put two wavefronts on every SIMD.
+    if (p.attend_blocks <= TWO_STREAM_MAX_BLOCKS && a.t_k >= TWO_STREAM_MIN_TOKENS) {
+      const hipError_t e = allow_two_stream_lds();
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(attend_bf16_d128_kernel<2>, grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
+    } else {
+      hipLaunchKernelGGL(attend_bf16_d128_kernel<1>, grid, dim3(256), 0, stream, p);
+    }
   } else {
     p.n_qtiles = (a.t_k + FQ - 1) / FQ;
     p.attend_blocks = int(unsigned(p.n_qtiles) * a.H * a.batch);

@@ -160,6 +160,15 @@ def test_bf16_fused_attend_append_medium():
     _bf16_case(1, 6, (1, 2, 4, 6, 8, 12, 16, 20, 24, 32), 3, 4, 2, seed=5, fused=True)
 
 
+def test_bf16_two_key_streams_per_workgroup():
+    # Launches that give every compute unit at most one workgroup use the instance with two key streams per
+    # workgroup (scales of 384 tokens and more).  Token counts 400, 441 and 529 with ragged query and key tiles:
+    # heads whose walk has an odd number of tiles leave the second stream idle in the last step, the last query
+    # tile has idle wavefronts, and the two streams merge partial sums taken against different references.
+    _bf16_case(1, 5, (1, 2, 4, 20, 21, 23), 2, 3, 2, seed=21, fused=True)
+    _bf16_case(2, 3, (1, 3, 20, 22), 1, 2, 1, seed=22)
+
+
 def test_bf16_layer2b_full_size():
     # One Infinity-2B-like layer at its real shape (16 heads, 13 scales, batch 2, 4x budget).
     cfg = hi.CONFIGS["layer2b"]
