@@ -235,6 +235,17 @@ def test_calibrate_scales_argument_checks():
         hk.heatkv_calibrate_scales_accumulate(shape, 0, [1, 2], [None], [None, None], 0.125, 1.0, None, None, None)
 
 
+def test_bench_refuses_more_than_one_gpu_before_touching_any():
+    # one GPU only: the benchmark says so and exits instead of starting ranks
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
+
+
 def test_full_budget_plan_keeps_everything():
     t0 = hi.tokens_per_scale(hi.SIDES_TINY)
     c = hi.cumulative_tokens(t0)
