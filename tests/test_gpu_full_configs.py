@@ -27,21 +27,31 @@ def _calibrate_stack(cfg, shape, w, t0, c, sm, n_sets, seed, rng, n_mass_samples
     mass = torch.empty(nb, H, K, device=DEV)
     ws = [torch.empty(max(binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device=DEV)
           for k1 in range(K)]
+    mass_all = [torch.empty(nb, H, K, device=DEV) for _ in range(K)]
+    ws_all = torch.empty(binding.calibrate_scales_workspace_bytes(shape, list(range(K))), dtype=torch.uint8, device=DEV)
     picks = {(int(rng.integers(n_sets)), int(rng.integers(L)), int(rng.integers(K))) for _ in range(n_mass_samples)}
+    picks.add((1 % n_sets, L - 1, K - 1))
     picks.add((0, 0, K - 1))
     checks = []
     for st in range(n_sets):
         for l in range(L):
             q, k, _ = hi.make_qkv_device(seed + st, l, cfg, w, DEV)
+            qs = [q[:, :, c[k1] - t0[k1]:c[k1]].contiguous() for k1 in range(K)]
+            kas = [k[:, :, :c[k1]].contiguous() for k1 in range(K)]
+            if st % 2:  # odd sets: all scales of the layer in one launch, masses kept per scale
+                hk.heatkv_calibrate_scales_accumulate(shape, l, list(range(K)), qs, kas, sm, 1.0 / (n_sets * nb),
+                                                      beta, mass_all, ws_all)
             for k1 in range(K):
-                qk = q[:, :, c[k1] - t0[k1]:c[k1]].contiguous()
-                ka = k[:, :, :c[k1]].contiguous()
-                hk.heatkv_calibrate(shape, l, k1, qk, ka, sm, mass, ws[k1])
-                hk.heatkv_accumulate_beta(shape, l, k1, mass, 1.0 / (n_sets * nb), beta)
-                hk.heatkv_accumulate_beta(shape, l, k1, mass, 1.0 / nb, beta_sets[st])
+                if st % 2:
+                    m = mass_all[k1]
+                else:
+                    m = mass
+                    hk.heatkv_calibrate(shape, l, k1, qs[k1], kas[k1], sm, mass, ws[k1])
+                    hk.heatkv_accumulate_beta(shape, l, k1, mass, 1.0 / (n_sets * nb), beta)
+                hk.heatkv_accumulate_beta(shape, l, k1, m, 1.0 / nb, beta_sets[st])
                 if (st, l, k1) in picks:
                     b, h = int(rng.integers(nb)), int(rng.integers(H))
-                    checks.append((k1, mass[b, h].cpu().double().numpy(), q[b, h].cpu(), k[b, h].cpu()))
+                    checks.append((k1, m[b, h].cpu().double().numpy(), q[b, h].cpu(), k[b, h].cpu()))
     torch.cuda.synchronize()
     return beta.cpu().numpy(), checks, beta_sets.cpu().numpy()
 
