@@ -169,6 +169,28 @@ def test_bf16_two_key_streams_per_workgroup():
     _bf16_case(2, 3, (1, 3, 20, 22), 1, 2, 1, seed=22)
 
 
+def test_bf16_budget_extremes():
+    # Full budget: nothing is pruned, every head walks all prior scales (the longest runs the layout can hold).
+    # Smallest legal budget (the sink scales only): every head keeps just the sinks.  Both at sizes that use the
+    # two-stream instance (400 and 484 tokens) and the plain one.
+    sides = (1, 2, 4, 9, 20, 22)
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    _bf16_case(1, 2, sides, 2, 1, 1, seed=25)                     # den = 1: B = all prior tokens
+    L, H, s = 1, 3, 2
+    K = len(t0)
+    w = hi.head_weights(26, L, H, K)
+    beta0 = hi.expected_beta_from_weights(w, t0).astype(np.float32)
+    shape = hk.Shape(L, H, 128, t0, 2, "bf16")
+    plan = hk.heatkv_build_schedule(shape, beta0, L * H * c[s - 1] * 2 * 128 * 2, s)
+    assert plan.N().tolist()[s:K - 1] == [L * H] * (K - 1 - s)
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, L * H * c[s - 1])
+    cfg = dict(L=L, H=H, d=128, dtype="bf16", batch=2, sides=sides)
+    q, k, v = hi.make_qkv(26, 0, cfg, w=w)
+    outs = device_generation(plan, 0, *_dev(q, k, v), t0, 1.0 / np.sqrt(128), fused=True)
+    _check_all(outs, q, k, v, t0, ref["present"], 0, 1.0 / np.sqrt(128), TOL["bf16"])
+
+
 def test_bf16_layer2b_full_size():
     # One Infinity-2B-like layer at its real shape (16 heads, 13 scales, batch 2, 4x budget).
     cfg = hi.CONFIGS["layer2b"]
