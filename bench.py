@@ -250,6 +250,7 @@ def main():
         result["roofline"]["frac_of_probe_random"] = round(att_tflops / probe["random_operands"], 4)
         result["roofline"]["largest_scale_frac_of_probe_random"] = round(
             att_flops[K - 1] / (att_ms_k[K - 1] * 1e-3) / 1e12 / probe["random_operands"], 4)
+        result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -306,6 +307,39 @@ def mfma_probe(dev):
         ms = e0.elapsed_time(e1)
         best = ms if best is None else min(best, ms)
     res["attention_tile_step_model"] = round(workgroups * 4 * t_iters * 32 * 32768.0 / best / 1e9, 1)
+    return res
+
+
+def hbm_read_probe(dev):
+    """Read bandwidth of the attention kernel's own access pattern with the arithmetic taken out (tile copies
+    HBM -> LDS, two stages, a barrier per step, two workgroups per compute unit): a long walk (1024 workgroups x
+    64 steps = 2 GiB) and walks as short as those of the scales bound by the K/V read (1024 workgroups x 9 steps,
+    each launch on memory it has not touched before)."""
+    import torch
+
+    import paper_2605_14877_amd as hk
+
+    wgs = 1024
+    src = torch.empty(hk.heatkv_probe_tile_stream_bytes(wgs, 64), dtype=torch.uint8, device=dev)
+    src.random_(0, 256)
+    out = torch.empty(wgs * 256, dtype=torch.int32, device=dev)
+    res = {"unit": "GB/s", "workgroups": wgs}
+
+    def best_of(n, steps, offset_steps):
+        best = None
+        for i in range(n):
+            part = src[i * offset_steps * wgs * 32768:]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            hk.heatkv_probe_tile_stream(part, out, wgs, steps)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return round(hk.heatkv_probe_tile_stream_bytes(wgs, steps) / best / 1e6, 1)
+
+    res["walk_64_steps"] = best_of(4, 64, 0)
+    res["walk_9_steps"] = best_of(6, 9, 9)  # six disjoint 288 MiB parts of the buffer, none read twice in a row
     return res
 
 
@@ -408,6 +442,7 @@ def run_stack(args, dev):
         probe = mfma_probe(dev)
         result["roofline"]["mfma_probe"] = probe
         result["roofline"]["frac_of_probe_random"] = round(float(value) / probe["random_operands"], 4)
+        result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
     print(json.dumps(result))
 
 

@@ -276,6 +276,20 @@ int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iter
 size_t heatkv_probe_tile_step_bytes(void);
 int heatkv_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, void* stream);
 
+/*
+ * Measurement aid, not a step of the method: the attention kernel's way of reading memory with the arithmetic
+ * taken out.  `workgroups` x 256 threads; workgroup w copies `steps` consecutive 32 KB steps (a K and a V tile),
+ * starting at byte w * steps * 32768 of `src`, from device memory into LDS with the kernel's copy instructions,
+ * two stages, one wait and one workgroup barrier per step, two workgroups per compute unit.  Its rate,
+ * heatkv_probe_tile_stream_bytes(workgroups, steps) bytes over the time the caller measures, is the read
+ * bandwidth this access pattern can reach on the GPU at hand.  `src`: device, src_bytes >= that many bytes;
+ * `out`: device, workgroups x 256 words, word [w][i] = XOR over the steps of 32-bit word i of each step
+ * (the copies keep the byte order, so the caller can check it).  Asynchronous on `stream`.  HEATKV_EINVAL for null
+ * pointers, sizes out of range (1 .. 2^20 each) or a source that is too small.
+ */
+size_t heatkv_probe_tile_stream_bytes(int workgroups, int steps);
+int heatkv_probe_tile_stream(const void* src, size_t src_bytes, uint32_t* out, int workgroups, int steps, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

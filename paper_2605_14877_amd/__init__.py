@@ -29,5 +29,7 @@ from .binding import (  # noqa: F401
     heatkv_probe_mfma_operand_bytes,
     heatkv_probe_tile_step,
     heatkv_probe_tile_step_bytes,
+    heatkv_probe_tile_stream,
+    heatkv_probe_tile_stream_bytes,
     library_path,
 )

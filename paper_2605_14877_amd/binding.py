@@ -63,6 +63,10 @@ def lib():
     L.heatkv_calibrate_scales_accumulate.restype = C.c_int
     L.heatkv_calibrate_scales_accumulate.argtypes = [sp, C.c_int, C.c_int, i32p, C.POINTER(vp), C.POINTER(vp),
                                                      C.c_float, C.c_float, vp, C.POINTER(vp), vp, C.c_size_t, vp]
+    L.heatkv_probe_tile_stream_bytes.restype = C.c_size_t
+    L.heatkv_probe_tile_stream_bytes.argtypes = [C.c_int, C.c_int]
+    L.heatkv_probe_tile_stream.restype = C.c_int
+    L.heatkv_probe_tile_stream.argtypes = [vp, C.c_size_t, vp, C.c_int, C.c_int, vp]
     L.heatkv_accumulate_beta.restype = C.c_int
     L.heatkv_accumulate_beta.argtypes = [sp, C.c_int, C.c_int, vp, C.c_float, vp, vp]
     L.heatkv_build_schedule.restype = C.c_int
@@ -368,6 +372,19 @@ def heatkv_calibrate_scales_accumulate(shape, layer, k1_list, q_list, k_all_list
     _check(lib().heatkv_calibrate_scales_accumulate(shape.ref, layer, n, k1, qp, kp, float(sm_scale), float(weight),
                                                     _ptr(beta), mp, _ptr(ws), ws_bytes,
                                                     _stream() if stream is None else stream))
+
+
+def heatkv_probe_tile_stream_bytes(workgroups, steps):
+    return int(lib().heatkv_probe_tile_stream_bytes(int(workgroups), int(steps)))
+
+
+def heatkv_probe_tile_stream(src, out, workgroups, steps, stream=None):
+    """Measurement aid: the attention kernel's HBM -> LDS tile copies without arithmetic (see include/heatkv.h)."""
+    _check_tensor(src, "src")
+    _check_tensor(out, "out", min_bytes=max(int(workgroups), 0) * 256 * 4)
+    src_bytes = 0 if src is None else src.numel() * src.element_size()
+    _check(lib().heatkv_probe_tile_stream(_ptr(src), src_bytes, _ptr(out), int(workgroups), int(steps),
+                                          _stream() if stream is None else stream))
 
 
 def heatkv_probe_mfma_operand_bytes():

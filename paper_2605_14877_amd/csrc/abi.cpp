@@ -471,4 +471,19 @@ int heatkv_probe_tile_step(const void* tiles, float* out, int workgroups, int it
   return HEATKV_OK;
 }
 
+size_t heatkv_probe_tile_stream_bytes(int workgroups, int steps) {
+  if (workgroups <= 0 || workgroups > (1 << 20) || steps <= 0 || steps > (1 << 20)) return 0;
+  return heatkv::probe_tile_stream_bytes(workgroups, steps);
+}
+
+int heatkv_probe_tile_stream(const void* src, size_t src_bytes, uint32_t* out, int workgroups, int steps, void* stream) {
+  if (!src || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
+  const size_t need = heatkv_probe_tile_stream_bytes(workgroups, steps);
+  if (need == 0) return fail(HEATKV_EINVAL, "probe size out of range");
+  if (src_bytes < need) return fail(HEATKV_EINVAL, "probe source smaller than workgroups x steps x 32 KB");
+  hipError_t e = heatkv::launch_probe_tile_stream(src, out, workgroups, steps, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "probe_tile_stream launch");
+  return HEATKV_OK;
+}
+
 }  // extern "C"

@@ -190,7 +190,50 @@ __global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv,
   out[blockIdx.x * 256 + tid] = acc;
 }
 
+// Tile stream: the attention kernel's way of reading (HBM -> LDS copies of 1 KB per wavefront and instruction,
+// two stages of a K and a V tile, a wait and a workgroup barrier per step, two workgroups per compute unit) with
+// no arithmetic at all.  Workgroup w walks `steps` consecutive 32 KB steps of its own part of `src`; every thread
+// folds one word of each landed step into a checksum, which is all it computes.
+__global__ __launch_bounds__(256, 2) void probe_tile_stream_kernel(const char* src, int steps, unsigned* out) {
+  __shared__ __attribute__((aligned(1024))) char lds[2][2 * kTileBytes];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const unsigned lds_base =
+      static_cast<unsigned>(reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0][0])));
+  const unsigned off = lane * 16;
+  const char* base = src + static_cast<size_t>(blockIdx.x) * steps * (2 * kTileBytes);
+  auto issue = [&](int t) {
+    const char* s = base + static_cast<size_t>(t) * (2 * kTileBytes);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const unsigned dst = lds_base + (t & 1) * (2 * kTileBytes) + (4 * j + wave) * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(s + (4 * j + wave) * 1024)
+                   : "memory");
+    }
+  };
+  issue(0);
+  unsigned acc = 0;
+  for (int t = 0; t < steps; ++t) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t + 1 < steps) issue(t + 1);
+    acc ^= *reinterpret_cast<const unsigned*>(&lds[t & 1][tid * 4]);
+    // the stage read here is overwritten by the copy of step t + 2, which is issued after the next barrier
+  }
+  out[blockIdx.x * 256 + tid] = acc;
+}
+
 }  // namespace
+
+size_t probe_tile_stream_bytes(int workgroups, int steps) {
+  return size_t(workgroups) * size_t(steps) * (2 * kTileBytes);
+}
+
+hipError_t launch_probe_tile_stream(const void* src, unsigned* out, int workgroups, int steps, hipStream_t stream) {
+  hipLaunchKernelGGL(probe_tile_stream_kernel, dim3(workgroups), dim3(256), 0, stream, static_cast<const char*>(src),
+                     steps, out);
+  return hipGetLastError();
+}
 
 size_t probe_tile_step_bytes() { return size_t(2) * kModelTiles * kTileBytes; }
 

@@ -475,3 +475,25 @@ def test_tile_step_probe_runs_and_is_deterministic():
         hk.heatkv_probe_tile_step(tiles, out1, 6, 3)  # odd step count
     with pytest.raises(ValueError):
         hk.heatkv_probe_tile_step(tiles[:100], out1, 6, 4)
+
+
+def test_tile_stream_probe_copies_what_it_claims():
+    # The read-bandwidth probe is the attention kernel's tile copy without arithmetic; its checksum words prove
+    # that every step of every workgroup went through LDS in source order.
+    wgs, steps = 6, 5
+    nbytes = hk.heatkv_probe_tile_stream_bytes(wgs, steps)
+    assert nbytes == wgs * steps * 32768
+    g = torch.Generator(device="cuda").manual_seed(7)
+    src = torch.randint(-2**31, 2**31 - 1, (wgs, steps, 8192), dtype=torch.int32, device="cuda", generator=g)
+    out = torch.zeros(wgs, 256, dtype=torch.int32, device="cuda")
+    hk.heatkv_probe_tile_stream(src, out, wgs, steps)
+    torch.cuda.synchronize()
+    want = src[:, 0, :256].clone()
+    for t in range(1, steps):
+        want ^= src[:, t, :256]
+    assert torch.equal(out, want)
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_probe_tile_stream(src, out, wgs, steps + 1)  # source too small
+    with pytest.raises(hk.HeatKVError):
+        hk.heatkv_probe_tile_stream(src, out, 0, steps)
+
