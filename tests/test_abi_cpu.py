@@ -83,6 +83,7 @@ def test_planner_bit_exact_on_named_configs(name):
     (3, 5, 3, (1, 2, 4, 6, 8, 12), 1, 1, 3),
     (4, 1, 4, hi.SIDES_TINY, 1, 1, 2),
     (5, 6, 1, (1, 2, 4, 6, 8), 0, 2, 5),
+    (6, 2, 3, tuple(range(1, 32)), 3, 1, 5),   # 31 scales: the largest K the ABI takes
 ])
 def test_planner_bit_exact_on_random_beta_all_variants(variant, seed, L, H, sides, s, num, den):
     t0 = hi.tokens_per_scale(sides)
@@ -96,6 +97,14 @@ def test_planner_bit_exact_on_random_beta_all_variants(variant, seed, L, H, side
     plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * 64 * 4, s, variant)
     ref = harness.oracle_schedule(beta0, L, H, t0, s, B, variant)
     _compare(plan, ref, K, L, H, s)
+
+
+def test_more_scales_than_the_abi_takes_are_rejected():
+    t0 = hi.tokens_per_scale(tuple(range(1, 33)))  # 32 scales
+    assert len(t0) == 32
+    with pytest.raises(hk.HeatKVError) as e:
+        hk.heatkv_build_schedule(hk.Shape(1, 2, 64, t0, 1, "f32"), harness.random_beta(0, 1, 2, 32), 1 << 30, 2)
+    assert e.value.code == -1
 
 
 def test_layout_is_a_valid_fifo_and_respects_the_budget_accounting():

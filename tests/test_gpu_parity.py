@@ -191,6 +191,35 @@ def test_bf16_budget_extremes():
     _check_all(outs, q, k, v, t0, ref["present"], 0, 1.0 / np.sqrt(128), TOL["bf16"])
 
 
+def test_bf16_thirty_one_scales():
+    # The largest scale count the ABI takes (the kernel parameter tables are sized for it): schedule, attention
+    # against the oracle, and all 31 scales calibrated in one launch against the per-scale calls.
+    sides = tuple(range(1, 32))
+    _bf16_case(1, 2, sides, 3, 3, 1, seed=27, sample_from=12)
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K, H, d, batch = len(t0), 2, 128, 1
+    sm = 1.0 / np.sqrt(d)
+    g = torch.Generator().manual_seed(28)
+    q = torch.randn(batch, H, c[-1], d, generator=g).to(torch.bfloat16)
+    k = torch.randn(batch, H, c[-1], d, generator=g).to(torch.bfloat16)
+    dq, dk = _dev(q, k)
+    shape = hk.Shape(1, H, d, t0, batch, "bf16")
+    qs = [dq[:, :, c[i] - t0[i]:c[i]].contiguous() for i in range(K)]
+    ks = [dk[:, :, :c[i]].contiguous() for i in range(K)]
+    beta_a = torch.zeros(1, H, K, K, device="cuda")
+    beta_b = torch.zeros(1, H, K, K, device="cuda")
+    for k1 in range(K):
+        ws = torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device="cuda")
+        hk.heatkv_calibrate_accumulate(shape, 0, k1, qs[k1], ks[k1], sm, 1.0, beta_a, None, ws)
+    ws = torch.empty(hk.binding.calibrate_scales_workspace_bytes(shape, list(range(K))), dtype=torch.uint8, device="cuda")
+    hk.heatkv_calibrate_scales_accumulate(shape, 0, list(range(K)), qs, ks, sm, 1.0, beta_b, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(beta_a, beta_b)
+    rows = beta_b[0].sum(-1).cpu().numpy()
+    assert np.abs(rows - 1.0).max() <= 1e-4  # every query scale's masses sum to one
+
+
 def test_bf16_layer2b_full_size():
     # One Infinity-2B-like layer at its real shape (16 heads, 13 scales, batch 2, 4x budget).
     cfg = hi.CONFIGS["layer2b"]
