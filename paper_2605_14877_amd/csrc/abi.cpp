@@ -66,6 +66,15 @@ int ensure_uploaded(heatkv_plan* p) {
     (void)hipFree(block);
     return hip_fail(e, "hipMemcpy");
   }
+  // Everything a launch may need to set up on this device happens here, not at the first launch, so that the
+  // launches themselves only enqueue kernels (a caller may be capturing them into a graph).
+  if (p->dtype == HEATKV_BF16) {
+    e = heatkv::attend_prepare_device();
+    if (e != hipSuccess) {
+      (void)hipFree(block);
+      return hip_fail(e, "attention kernel set-up");
+    }
+  }
   unsigned char* base = static_cast<unsigned char*>(block);
   p->dev.block = block;
   p->dev.work = reinterpret_cast<heatkv::HeadWork*>(base + o_work);

@@ -570,6 +570,8 @@ hipError_t allow_two_stream_lds() {
 
 }  // namespace
 
+hipError_t attend_prepare_device() { return allow_two_stream_lds(); }
+
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   AttendParams p{};
   p.H = a.H;

@@ -74,6 +74,9 @@ hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, co
 // attention kernel does, no arithmetic; out receives workgroups x 256 checksum words.
 size_t probe_tile_stream_bytes(int workgroups, int steps);
 hipError_t launch_probe_tile_stream(const void* src, unsigned* out, int workgroups, int steps, hipStream_t stream);
+// One-time set-up of the attention kernels on the current device (the LDS limit of the two-stream instance);
+// called at plan upload, repeated calls are cheap.
+hipError_t attend_prepare_device();
 size_t probe_mfma_operand_bytes();
 hipError_t launch_probe_mfma(const void* operands, float* out, int workgroups, int iters, hipStream_t stream);
 // Tile-step model of the bf16 attention kernel: `workgroups` x 4 wavefronts each run `iters` (even) model steps of

@@ -372,7 +372,8 @@ def test_generation_pass_replays_from_a_hip_graph():
     # Once the plan is uploaded the entry points only enqueue kernels on the caller's stream, so a whole
     # generation pass can be captured and replayed; every replay must reproduce the eager results bit for bit,
     # also with other work and synchronisations between the replays.
-    sides, L, H, d, batch, s = (1, 2, 4, 6, 8, 12, 16), 1, 4, 128, 2, 2
+    # (the last two scales, 400 and 484 tokens, use the kernel instance with two key streams per workgroup)
+    sides, L, H, d, batch, s = (1, 2, 4, 6, 8, 12, 16, 20, 22), 1, 4, 128, 2, 2
     t0 = hi.tokens_per_scale(sides)
     c = hi.cumulative_tokens(t0)
     K = len(t0)
