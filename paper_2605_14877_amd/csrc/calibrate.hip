@@ -12,6 +12,7 @@
 // per (head, query tile); a second kernel adds the partials in tile order, so
 // the result is bit-reproducible (no floating-point atomics anywhere).
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "device_util.h"
@@ -54,9 +55,18 @@ __device__ __forceinline__ int scale_of_block(const CalibParams& p, int block) {
 // ---------------------------------------------------------------------------
 // bf16, d = 128: S^T = K Q^T on the matrix cores, one lane per query column
 // (same operand layout, LDS tile format and HBM -> LDS copy as the attention
-// kernel), 128 queries per workgroup, up to three workgroups per compute unit.
+// kernel).  Two instances.  CSETS = 1: 128 queries per workgroup, one set of 32 per
+// wavefront, three workgroups per compute unit.  CSETS = 2: 256 queries per
+// workgroup; every wavefront owns two sets of 32 (rows w*32 + n and 128 + w*32 + n
+// of the tile) and runs both against each K operand it has read from LDS, so a K
+// tile is copied and read once per 256 queries and the matrix-core work of one set
+// overlaps the exponentials of the other inside the wavefront; two workgroups per
+// compute unit.  On a full chip the two are equally fast (two wavefronts per SIMD
+// with twice the independent work against three); the launcher takes the second
+// when its workgroups fill their 512 slots at least once, which then needs fewer,
+// longer workgroups and ends with a shorter tail.
 // ---------------------------------------------------------------------------
-constexpr int CBM = 128;
+constexpr int CBM1 = 128;  // queries per set of four wavefronts
 constexpr int CBN = 64;
 constexpr int CD = 128;
 constexpr int CROW_BYTES = 256;
@@ -67,11 +77,13 @@ constexpr int CTILE_BYTES = CBN * CROW_BYTES;
 __device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
 
 // Dynamic LDS: two K tiles, then blk_sum[k1+1][128], blk_max[k1+1][128], fin_max[128] (floats).
-__host__ __device__ constexpr size_t calib_lds_bytes(int k1) {
-  return 2 * CTILE_BYTES + (2 * size_t(k1 + 1) + 1) * CBM * sizeof(float);
+__host__ __device__ constexpr size_t calib_lds_bytes(int k1, int csets) {
+  return 2 * CTILE_BYTES + (2 * size_t(k1 + 1) + 1) * (CBM1 * csets) * sizeof(float);
 }
 
-__global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams p) {
+template <int CSETS>
+__global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_kernel(CalibParams p) {
+  constexpr int CBM = CBM1 * CSETS;  // queries per workgroup
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const ScaleJob& job = p.job[scale_of_block(p, blockIdx.x)];
   const int k1 = job.k1, t_k1 = p.t[k1];
@@ -94,13 +106,16 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
 
   const char* kbase = reinterpret_cast<const char*>(static_cast<const bf16_t*>(job.k_all) +
                                                     static_cast<long long>(bh) * c_k1 * CD);
-  const int q_row = qt * CBM + wave * 32 + n;
-  bf16x8 qreg[8];
-  {
+  // The second set of a tile exists only if the tile reaches past its first 128 rows (workgroup-uniform).
+  const bool two_sets = CSETS == 2 && qt * CBM + 128 < t_k1;
+  bf16x8 qreg[CSETS][8];
+#pragma unroll
+  for (int qs = 0; qs < CSETS; ++qs) {
+    const int q_row = qt * CBM + qs * 128 + wave * 32 + n;
     const int ld = q_row < t_k1 ? q_row : t_k1 - 1;
     const bf16_t* qp = static_cast<const bf16_t*>(job.q) + (static_cast<long long>(bh) * t_k1 + ld) * CD + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < 8; ++ks) qreg[qs][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
   const float c = p.sm_scale * kLog2e;
 
@@ -132,7 +147,12 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * CROW_BYTES + (((2 * ks + hl) ^ swizzle_k(n)) << 4);
 
-  float m_run = -INFINITY, cur = 0.f;
+  float m_run[CSETS], cur[CSETS];
+#pragma unroll
+  for (int qs = 0; qs < CSETS; ++qs) {
+    m_run[qs] = -INFINITY;
+    cur[qs] = 0.f;
+  }
   int k2 = 0, tile = 0;  // the tile being computed
 
   auto tile_step = [&](auto buf_tag) {
@@ -146,75 +166,77 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
     if (nk2 <= k1) issue_tile(nk2, ntile, buf ^ 1);
     const char* kt = lds + buf * CTILE_BYTES;
 
-    f32x16 s[2];
     bf16x8 ka[2][8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
         ka[cb][ks] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * CROW_BYTES + k_off[ks]);
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-        s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[ks], s[cb], 0, 0, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-
     const int left = p.t[k2] - tile * CBN;
-    if (left < CBN) {
+#pragma unroll
+    for (int qs = 0; qs < CSETS; ++qs) {
+      if (qs == 1 && !two_sets) break;
+      f32x16 s[2];
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
-    }
-    // Probabilities are taken relative to the running reference m_run, which is only brought up to the true
-    // row maximum when it has fallen too far behind: as long as no score exceeds it by more than 8 in the
-    // base-2 exponent a lane's 32 probabilities of the tile sum to at most 2^13, so a larger sum, an infinity or
-    // a NaN (the first tile, where m_run is still -inf) sends the whole wavefront through the exact path, which
-    // finds the tile maximum, rescales what the block has summed so far and redoes the tile's exponentials.
-    // The masses are ratios of such sums, so they do not depend on the reference; the max chain, one vector
-    // instruction per two scores, leaves the common path.
-    float mc = m_run * c;
-    float rs[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+      for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) rs[r & 3] += fast_exp2(fmaf(s[cb][r], c, -mc));
-    float tile_sum = (rs[0] + rs[1]) + (rs[2] + rs[3]);
-    if (__any(!(tile_sum <= 8192.f))) {
-      float mx = s[0][0];
+        for (int cb = 0; cb < 2; ++cb)
+          s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[qs][ks], s[cb], 0, 0, 0);
+
+      if (left < CBN) {
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
-      mx = max_halves(mx);
-      const float m_new = fmaxf(m_run, mx);
-      cur *= fast_exp2((m_run - m_new) * c);
-      m_run = m_new;
-      mc = m_new * c;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) rs[i] = 0.f;
+          for (int r = 0; r < 16; ++r)
+            if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
+      }
+      // Probabilities are taken relative to the running reference m_run, which is only brought up to the true
+      // row maximum when it has fallen too far behind: as long as no score exceeds it by more than 8 in the
+      // base-2 exponent a lane's 32 probabilities of the tile sum to at most 2^13, so a larger sum, an infinity
+      // or a NaN (the first tile, where m_run is still -inf) sends the whole wavefront through the exact path,
+      // which finds the tile maximum, rescales what the block has summed so far and redoes the tile's
+      // exponentials.  The masses are ratios of such sums, so they do not depend on the reference; the max
+      // chain, one vector instruction per two scores, leaves the common path.
+      float mc = m_run[qs] * c;
+      float rs[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) rs[r & 3] += fast_exp2(fmaf(s[cb][r], c, -mc));
-      tile_sum = (rs[0] + rs[1]) + (rs[2] + rs[3]);
-    }
-    cur += tile_sum;
-
-    if (last_of_block) {
-      const float both = sum_halves(cur);
-      if (hl == 0) {
-        blk_sum[k2 * CBM + wave * 32 + n] = both;
-        blk_max[k2 * CBM + wave * 32 + n] = m_run;
+      float tile_sum = (rs[0] + rs[1]) + (rs[2] + rs[3]);
+      if (__any(!(tile_sum <= 8192.f))) {
+        float mx = s[0][0];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
+        mx = max_halves(mx);
+        const float m_new = fmaxf(m_run[qs], mx);
+        cur[qs] *= fast_exp2((m_run[qs] - m_new) * c);
+        m_run[qs] = m_new;
+        mc = m_new * c;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rs[i] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) rs[r & 3] += fast_exp2(fmaf(s[cb][r], c, -mc));
+        tile_sum = (rs[0] + rs[1]) + (rs[2] + rs[3]);
       }
-      cur = 0.f;
+      cur[qs] += tile_sum;
+
+      if (last_of_block) {
+        const float both = sum_halves(cur[qs]);
+        if (hl == 0) {
+          blk_sum[k2 * CBM + qs * 128 + wave * 32 + n] = both;
+          blk_max[k2 * CBM + qs * 128 + wave * 32 + n] = m_run[qs];
+        }
+        cur[qs] = 0.f;
+      }
     }
     k2 = nk2;
     tile = ntile;
@@ -227,11 +249,14 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
     tile_step(std::integral_constant<int, 1>{});
     if (k2 > k1) break;
   }
-  if (hl == 0) fin_max[wave * 32 + n] = m_run;
+  if (hl == 0) {
+#pragma unroll
+    for (int qs = 0; qs < CSETS; ++qs) fin_max[qs * 128 + wave * 32 + n] = m_run[qs];
+  }
   __syncthreads();
 
   // Row masses relative to the final maximum, normalised; rows past t_k1 contribute nothing.
-  if (tid < CBM) {
+  if (tid < 128 || two_sets) {  // one thread per query row of the tile; rows of an absent second set hold nothing
     const float mf = fin_max[tid];
     float l = 0.f;
     for (int j = 0; j <= k1; ++j) {
@@ -243,11 +268,18 @@ __global__ __launch_bounds__(256, 3) void calibrate_bf16_d128_kernel(CalibParams
     for (int j = 0; j <= k1; ++j) blk_sum[j * CBM + tid] *= inv;
   }
   __syncthreads();
+  // One partial per 128 query rows whichever the instance: a set of the two-set instance holds exactly the rows of
+  // one query tile of the other and sums them in the same order, so both write the same bits to the same places.
+  const int n_parts = (t_k1 + CBM1 - 1) / CBM1;
   for (int j = wave; j <= k1; j += 4) {
-    float v = blk_sum[j * CBM + lane] + blk_sum[j * CBM + lane + 64];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    if (lane == 0) job.partial[(static_cast<long long>(bh) * n_qtiles + qt) * p.K + j] = v;
+    for (int qs = 0; qs < CSETS; ++qs) {
+      if (qs == 1 && !two_sets) break;
+      float v = blk_sum[j * CBM + qs * CBM1 + lane] + blk_sum[j * CBM + qs * CBM1 + lane + 64];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+      if (lane == 0) job.partial[(static_cast<long long>(bh) * n_parts + CSETS * qt + qs) * p.K + j] = v;
+    }
   }
 }
 
@@ -394,7 +426,8 @@ __global__ void accumulate_beta_kernel(int H, int batch, int K, int layer, int k
   beta[((static_cast<long long>(layer) * H + h) * K + k1) * K + k2] += weight * v;
 }
 
-int queries_per_tile(int dtype) { return dtype == HEATKV_BF16 ? CBM : FQ; }
+// Query rows per partial sum.
+int queries_per_tile(int dtype) { return dtype == HEATKV_BF16 ? CBM1 : FQ; }
 
 }  // namespace
 
@@ -430,8 +463,17 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
   p.beta = a.beta;
   p.weight = a.weight;
   p.layer = a.layer;
-  const int qpt = queries_per_tile(a.dtype);
   const bool mfma = a.dtype == HEATKV_BF16;
+  // bf16: the instance with two query sets per wavefront if its workgroups fill their 512 slots at least once.
+  // Both leave one partial per 128 query rows (qpt), bit for bit the same ones.
+  const int qpt = queries_per_tile(a.dtype);
+  int rows_per_block = qpt;
+  if (mfma) {
+    unsigned long long wide_blocks = 0;
+    for (int i = 0; i < a.n_scales; ++i)
+      wide_blocks += (unsigned long long)((a.t[a.k1[i]] + 2 * CBM1 - 1) / (2 * CBM1)) * a.H * a.batch;
+    if (wide_blocks >= 512) rows_per_block = 2 * CBM1;
+  }
   if (mfma && a.d != 128) return hipErrorInvalidValue;
   if (!mfma && a.d != 64 && a.d != 128) return hipErrorInvalidValue;
   // Largest scale first: its workgroups are the long ones, the short ones then fill the gaps they leave.
@@ -452,12 +494,28 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
     job.k_all = a.k_all[src];
     job.partial = reinterpret_cast<float*>(static_cast<char*>(a.ws) + ws_off);
     job.mass = a.mass[src];
-    blocks += unsigned((a.t[job.k1] + qpt - 1) / qpt) * pairs;
+    blocks += unsigned((a.t[job.k1] + rows_per_block - 1) / rows_per_block) * pairs;
     ws_off += (calibrate_workspace_bytes(a.dtype, a.d, a.H, a.batch, a.K, a.t[job.k1]) + 255) / 256 * 256;
     k1_max = job.k1 > k1_max ? job.k1 : k1_max;
   }
-  if (mfma)
-    hipLaunchKernelGGL(calibrate_bf16_d128_kernel, dim3(blocks), dim3(256), calib_lds_bytes(k1_max), stream, p);
+  if (mfma) {
+    // Many scales need more than the default 64 KB of dynamic LDS for the parked block sums: raise the limit to
+    // what the largest scale count can ask for, once per device.
+    static std::atomic<unsigned long long> raised{0};  // one bit per device ordinal below 64
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !(raised.load(std::memory_order_acquire) >> dev & 1)) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&calibrate_bf16_d128_kernel<2>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, int(calib_lds_bytes(MAXK - 1, 2)));
+      if (e != hipSuccess) return e;
+      if (dev >= 0 && dev < 64) raised.fetch_or(1ull << dev, std::memory_order_release);
+    }
+    if (rows_per_block == CBM1)
+      hipLaunchKernelGGL(calibrate_bf16_d128_kernel<1>, dim3(blocks), dim3(256), calib_lds_bytes(k1_max, 1), stream, p);
+    else
+      hipLaunchKernelGGL(calibrate_bf16_d128_kernel<2>, dim3(blocks), dim3(256), calib_lds_bytes(k1_max, 2), stream, p);
+  }
   else if (a.d == 64)
     hipLaunchKernelGGL(calibrate_f32_kernel<64>, dim3(blocks), dim3(256), 0, stream, p);
   else

@@ -491,6 +491,42 @@ def test_calibrate_all_scales_in_one_launch_has_the_bits_of_the_per_scale_calls(
     assert np.abs(got - want).max() <= 1e-4
 
 
+def test_calibrate_instances_write_the_same_bits():
+    # The bf16 kernel has an instance with one and one with two query sets per wavefront; the launcher takes the
+    # second when its workgroups fill the chip.  Here the one-launch call over all scales gets the second (64
+    # pairs, 768 workgroups), every per-scale call the first; masses and beta must still agree bit for bit, and
+    # a large single scale (second instance) must agree with the oracle.
+    sides = (1, 2, 4, 6, 8, 12, 16, 20, 24)
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K, H, d, batch = len(t0), 16, 128, 4
+    sm = 1.0 / np.sqrt(d)
+    g = torch.Generator().manual_seed(43)
+    q = torch.randn(batch, H, c[-1], d, generator=g).to(torch.bfloat16)
+    k = torch.randn(batch, H, c[-1], d, generator=g).to(torch.bfloat16)
+    dq, dk = _dev(q, k)
+    shape = hk.Shape(1, H, d, t0, batch, "bf16")
+    qs = [dq[:, :, c[i] - t0[i]:c[i]].contiguous() for i in range(K)]
+    ks = [dk[:, :, :c[i]].contiguous() for i in range(K)]
+    beta_a = torch.zeros(1, H, K, K, device="cuda")
+    mass_a = [torch.empty(batch, H, K, device="cuda") for _ in range(K)]
+    for k1 in range(K):
+        ws = torch.empty(max(hk.binding.calibrate_workspace_bytes(shape, k1), 4), dtype=torch.uint8, device="cuda")
+        hk.heatkv_calibrate_accumulate(shape, 0, k1, qs[k1], ks[k1], sm, 0.25, beta_a, mass_a[k1], ws)
+    beta_b = torch.zeros(1, H, K, K, device="cuda")
+    mass_b = [torch.empty(batch, H, K, device="cuda") for _ in range(K)]
+    ws = torch.empty(hk.binding.calibrate_scales_workspace_bytes(shape, list(range(K))), dtype=torch.uint8, device="cuda")
+    hk.heatkv_calibrate_scales_accumulate(shape, 0, list(range(K)), qs, ks, sm, 0.25, beta_b, mass_b, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(beta_a, beta_b)
+    for k1 in range(K):
+        assert torch.equal(mass_a[k1], mass_b[k1]), k1
+    t1 = orc.one_based(t0)
+    for b, h in ((0, 0), (3, 15), (2, 7)):
+        want = orc.beta_row(q[b, h].double().numpy(), k[b, h].double().numpy(), t1, K, sm)[1:]
+        assert np.abs(mass_b[K - 1][b, h].cpu().double().numpy() - want).max() <= 1e-4
+
+
 def test_tile_step_probe_runs_and_is_deterministic():
     n = hk.heatkv_probe_tile_step_bytes() // 2
     g = torch.Generator(device="cuda").manual_seed(4)
