@@ -186,6 +186,10 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
           s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[qs][ks], s[cb], 0, 0, 0);
+      if (qs == 0) {  // all sixteen operand reads go out before the first MFMA instead of two at a time
+        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+      }
 
       if (left < CBN) {
 #pragma unroll
