@@ -8,9 +8,9 @@
 // end of a block the pair (sum, maximum at that moment) is parked in LDS; after
 // the last block every parked sum is rescaled to the final maximum, which gives
 // the row's normaliser and its per-block masses at once.  Row masses are then
-// summed over the workgroup's rows in a fixed order and written as one partial
-// per (head, query tile); a second kernel adds the partials in tile order, so
-// the result is bit-reproducible (no floating-point atomics anywhere).
+// summed over 128 rows at a time in a fixed order and written as one partial per
+// (head, 128 query rows); a second kernel adds the partials in row order, so the
+// result is bit-reproducible (no floating-point atomics anywhere).
 #include <algorithm>
 #include <atomic>
 #include <type_traits>
@@ -76,7 +76,8 @@ constexpr int CTILE_BYTES = CBN * CROW_BYTES;
 // of 16 consecutive rows; XORing the chunk with row % 16 spreads them over all 64 LDS banks.
 __device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
 
-// Dynamic LDS: two K tiles, then blk_sum[k1+1][128], blk_max[k1+1][128], fin_max[128] (floats).
+// Dynamic LDS: two K tiles, then blk_sum[k1+1][rows], blk_max[k1+1][rows], fin_max[rows] (floats), rows = the
+// queries of a workgroup.
 __host__ __device__ constexpr size_t calib_lds_bytes(int k1, int csets) {
   return 2 * CTILE_BYTES + (2 * size_t(k1 + 1) + 1) * (CBM1 * csets) * sizeof(float);
 }
