@@ -52,6 +52,8 @@ def main():
                     help="call heatkv_attend_scale and heatkv_append_scale separately instead of the fused entry point")
     ap.add_argument("--graph", action="store_true",
                     help="stack workloads only: capture one generation pass in a HIP graph and time its replays")
+    ap.add_argument("--no-stack-20x", action="store_true",
+                    help="default workload only: skip the two 20x stacks that supply the per-image attention time")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the matrix-core probe (back-to-back bf16 MFMAs on zero and on random operands, "
                          "run after the timed region and reported next to the roofline)")
@@ -251,6 +253,9 @@ def main():
         result["roofline"]["largest_scale_frac_of_probe_random"] = round(
             att_flops[K - 1] / (att_ms_k[K - 1] * 1e-3) / 1e12 / probe["random_operands"], 4)
         result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
+    if not args.no_stack_20x and not args.attend_only:
+        del ka, va
+        result["per_image_attention_ms_at_20x"] = per_image_ms_at_20x(args, dev)
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -345,6 +350,32 @@ def hbm_read_probe(dev):
 
 def run_stack(args, dev):
     """Generation-order attend + append over every layer of a stack config (no calibration pass)."""
+    result = stack_result(args, dev)
+    if not args.no_mfma_probe:
+        probe = mfma_probe(dev)
+        result["roofline"]["mfma_probe"] = probe
+        result["roofline"]["frac_of_probe_random"] = round(result["value"] / probe["random_operands"], 4)
+        result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
+    print(json.dumps(result))
+
+
+def per_image_ms_at_20x(args, dev):
+    """Per-image attention time over a whole stack at the 20x budget (the third figure of the headline metric):
+    the 8B-like stack (batch 2 = one image with its CFG row) and the serving stack (batch 32 = 16 images), one
+    warm-up pass and two timed passes each."""
+    import copy
+
+    out = {}
+    for name in ("stack8b", "serving"):
+        a = copy.copy(args)
+        a.workload, a.steps, a.warmup, a.graph, a.separate_append = name, 2, 1, False, False
+        r = stack_result(a, dev)
+        out[name] = {"ms_per_image": r["per_image_attention_ms"], "attend_tflops": r["value"],
+                     "images_per_pass": max(r["batch"] // 2, 1)}
+    return out
+
+
+def stack_result(args, dev):
     import torch
 
     import heatkv_inputs as hi
@@ -428,6 +459,7 @@ def run_stack(args, dev):
                                f"{cfg['factor']}x budget, sinks {s}; schedule from a fabricated beta table; "
                                f"attend + append only", "hip_graph": bool(args.graph)},
         "per_image_attention_ms": round(ms_per_step / max(nb // 2, 1), 4),
+        "batch": nb,
         "kv_cache_budget_mb": round(nb * B * 2 * d * esz / 1e6, 1),
         "arena_mb": round(2 * plan.arena_bytes / 1e6, 1),
         "arena_tokens_over_budget": round(plan.arena_tokens / B, 4),
@@ -438,12 +470,7 @@ def run_stack(args, dev):
                      "achieved": round(float(value), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(float(value) / PEAK_BF16_TFLOPS, 4), "traffic": None},
     }
-    if not args.no_mfma_probe:
-        probe = mfma_probe(dev)
-        result["roofline"]["mfma_probe"] = probe
-        result["roofline"]["frac_of_probe_random"] = round(float(value) / probe["random_operands"], 4)
-        result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
-    print(json.dumps(result))
+    return result
 
 
 def cpu_baseline(q, k, v, t0, plan, sm, d):
