@@ -14,17 +14,23 @@ Pins (tests/test_oracle_*.py): attention against brute-force masked attention
 of the whole sequence, against torch's scaled_dot_product_attention in fp64,
 Q = 0 closed forms, permutation and shift invariance; masses against row sums
 and the Q = 0 closed form; Eq. 5 against exact rational arithmetic and the
-total-cache identity; Alg. 1 against a hand-worked example
-(tests/golden/alg1_hand_example.txt), the budget/containment invariants, and,
-for the binary variant, brute-force minimum cardinality (Prop. 1); the rank
-dispersion of App. C against closed forms (identical runs, reversed orders)
-and against numpy's argsort/std on random tables.
+total-cache identity; Alg. 1, scale-dependent form, against a hand-worked
+example (tests/golden/alg1_hand_example.txt) and the budget/containment
+invariants; Alg. 1, binary form, against a second hand-worked example
+(tests/golden/alg1_binary_hand_example.txt, which also carries the Naive
+policy on the same instance), against the total of Sec. 3.2,
+N_k c_s + (T - N_k) c_k, after every layer, against the closed form of E_k
+that Eq. 5 and that total imply (every newly pruned head outside the first
+layer is pruned early, none of the first layer is), against a replay of the
+cache contents head by head, and brute-force minimum cardinality (Prop. 1);
+the rank dispersion of App. C against closed forms (identical runs, reversed
+orders) and against numpy's argsort/std on random tables.
 Minimum cardinality of E_k is not a property of the scale-dependent variant
 (the paper proves it for the binary case only): a hand-worked instance,
-tests/golden/alg1_scale_dependent_not_minimal.txt, has the printed greedy
-order pop three head-scales where two suffice.  There the algorithm's steps
-are followed as printed and pinned by the two hand-worked examples and the
-invariants.  No function of this file is left without a pin.
+tests/golden/alg1_scale_dependent_not_minimal.txt, has the greedy order of
+Alg. 1 pop three head-scales where two suffice.  There the algorithm's steps
+are followed in the paper's order and pinned by the hand-worked examples and
+the invariants.
 """
 from __future__ import annotations
 
@@ -299,9 +305,10 @@ class _Sets:
 
 
 def cached_tokens_scale_dependent(k, t, c, s, P):
-    """CachedTokens (scale-dependent form) for every head at once.
+    """Tokens each head holds once scale k is in, scale-dependent form (App. A), all heads at once.
 
-    c_s + sum_{i=s+1..k} t_i * 1[(i,l,h) not in P]  ->  array [L+1, H+1].
+    The sinks (c_s tokens) plus t_i for every source scale s < i <= k whose head-scale (i,l,h) is not in
+    the pruned set P  ->  array [L+1, H+1].
     """
     out = np.full(P.m.shape[1:], c[s], dtype=np.int64)
     for i in range(s + 1, k + 1):
@@ -310,53 +317,52 @@ def cached_tokens_scale_dependent(k, t, c, s, P):
 
 
 def cached_tokens_binary(k, t, c, s, P):
-    """CachedTokens (binary form): c_s if (l,h) in P else c_k.  P.m[0] carries the head set."""
+    """Tokens each head holds once scale k is in, binary form (App. A): a head of the pruned set P holds
+    the sinks only (c_s), any other head everything up to scale k (c_k).  P.m[0] carries the head set."""
     return np.where(P.m[0], c[s], c[k]).astype(np.int64)
 
 
 def cache_size_after_layer(k, layer, G_k, G_km1, E_k, t, c, s, L, H, binary=False):
-    """Alg. 2: total cached tokens once layers 1..layer of scale k have run.
+    """Alg. 2 (App. A): the cache total the budget is checked against after `layer` of scale k has run.
 
-    Layers already executed have applied all scale-k removals (G_k); later
-    layers only those made before scale k (A_k = G_{k-1} u E_k).
+    A layer that has run holds what it will hold at the end of the scale (everything in G_k is gone from
+    it); a layer that has not run yet is only missing what was taken out before the scale started,
+    G_{k-1} and the early-pruned set E_k.  Both per-head tables count scale k itself as cached.
     """
-    A_k = G_km1.union(E_k)
-    fn = cached_tokens_binary if binary else cached_tokens_scale_dependent
-    done = fn(k, t, c, s, G_k)
-    todo = fn(k, t, c, s, A_k)
-    M = 0
-    for lp in range(1, L + 1):
-        for h in range(1, H + 1):
-            M += int(done[lp, h]) if lp <= layer else int(todo[lp, h])
-    return M
+    gone_before_scale = G_km1.union(E_k)
+    count = cached_tokens_binary if binary else cached_tokens_scale_dependent
+    per_head_run = count(k, t, c, s, G_k)                  # [L+1, H+1]
+    per_head_pending = count(k, t, c, s, gone_before_scale)
+    return int(per_head_run[1:layer + 1, 1:H + 1].sum() + per_head_pending[layer + 1:L + 1, 1:H + 1].sum())
 
 
 def greedy_early_pruning(k, G_km1, G_k, B, rank, t, c, s, L, H, binary=False, naive=False):
-    """GreedyEarlyPruning of Alg. 1.  Returns (E_k as _Sets, list of popped items in order).
+    """The early-pruning step of Alg. 1 (Sec. 3.3).  Returns (E_k as _Sets, the items in the order taken).
 
-    Candidates G_k minus G_{k-1} are sorted by layer descending, source scale
-    descending, rank in O_i ascending, and taken from the front while the
-    simulated cache size after any layer exceeds B.  `naive` is the boundary
-    policy of Sec. 4.2 ("Pruning Algorithm"): E_k = G_k minus G_{k-1}.
+    The head(-scale)s that scale k newly marks for removal, G_k minus G_{k-1}, are queued deepest layer
+    first, then latest source scale first, then lowest rank in their order first.  Walking the layers in
+    execution order, the queue's front is moved into E_k for as long as the total of Alg. 2 after that layer
+    is above the budget B.  `naive` is the boundary policy of Sec. 4.2 ("Pruning Algorithm"): the whole
+    queue is pruned early, E_k = G_k minus G_{k-1}.
     """
     K = len(t) - 1
-    cand = [it for it in G_k.items() if it not in G_km1]
-    R = sorted(cand, key=lambda it: (-it[1], -it[0], rank[it]))
+    fresh = [it for it in G_k.items() if it not in G_km1]
+    queue = sorted(fresh, key=lambda it: (-it[1], -it[0], rank[it]))
     E = _Sets(K, L, H)
-    popped = []
+    taken = []
     if naive:
-        for it in R:
+        for it in queue:
             E.add(it)
-            popped.append(it)
-        return E, popped
+            taken.append(it)
+        return E, taken
     for layer in range(1, L + 1):
         while cache_size_after_layer(k, layer, G_k, G_km1, E, t, c, s, L, H, binary) > B:
-            if not R:
+            if not queue:
                 raise ValueError("early pruning cannot reach the budget")
-            it = R.pop(0)
+            it = queue.pop(0)
             E.add(it)
-            popped.append(it)
-    return E, popped
+            taken.append(it)
+    return E, taken
 
 
 def heatkv_schedule(orders, N, t, s, L, H, B, naive=False):

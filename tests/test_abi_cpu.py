@@ -349,3 +349,38 @@ def test_binding_rejects_wrong_operands_before_any_gpu_call():
         hk.heatkv_attend_scale(plan, 0, 1, np.zeros(4), None, None, None, None, 0.125, None, stream=0)
     with pytest.raises(ValueError, match="device tensor"):
         hk.heatkv_calibrate(shape, 0, 1, good, good, 0.125, good, None, stream=0)
+
+
+@pytest.mark.parametrize("variant", [binding.VARIANT_BINARY, binding.VARIANT_BINARY_NAIVE])
+def test_library_binary_variants_on_the_hand_worked_instance(variant):
+    # the instance of tests/golden/alg1_binary_hand_example.txt, checked against the pencil-worked sets directly
+    L, H, s, B = 3, 2, 1, 39
+    t0 = [1, 2, 4, 6, 9]
+    K, T = len(t0), L * H
+    order = [(2, 2), (1, 1), (3, 2), (2, 1), (1, 2), (3, 1)]  # O = [d, a, f, c, b, e], 1-based (layer, head)
+    beta0 = np.zeros((L, H, K, K), dtype=np.float32)
+    for r, (l, h) in enumerate(order):  # CAS = sum over tau in (s, K) of beta[K][tau]: rising along the order
+        beta0[l - 1, h - 1, K - 1, s:K - 1] = 0.01 * (r + 1)
+    shape = hk.Shape(L, H, 64, t0, 1, "f32")
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * 64 * 4, s, variant)
+    assert plan.N().tolist() == [0, 0, 1, 4]
+    assert plan.order(s).tolist() == [(l - 1) * H + (h - 1) for (l, h) in order]
+
+    def heads(k0, which):  # 1-based (layer, head) of the heads the set names at 0-based scale k0
+        bm = plan.sets(k0, which)
+        assert all(np.array_equal(bm[s], bm[i]) for i in range(s, K - 1)) and not bm[:s].any() and not bm[K - 1].any()
+        return sorted((head // H + 1, head % H + 1) for head in range(T) if bm[s, head])
+
+    assert heads(2, binding.SET_G) == [(2, 2)]
+    assert heads(3, binding.SET_G) == [(1, 1), (2, 1), (2, 2), (3, 2)]
+    assert heads(2, binding.SET_E) == [(2, 2)]
+    if variant == binding.VARIANT_BINARY:
+        assert heads(3, binding.SET_E) == [(2, 1), (3, 2)]
+        assert heads(3, binding.SET_A) == [(2, 1), (2, 2), (3, 2)]
+    else:
+        assert heads(3, binding.SET_E) == [(1, 1), (2, 1), (3, 2)]
+        assert heads(3, binding.SET_A) == [(1, 1), (2, 1), (2, 2), (3, 2)]
+    assert heads(4, binding.SET_A) == [(1, 1), (2, 1), (2, 2), (3, 2)]
+    # head (1,1) at paper scale 4 keeps scales 1-3 under Binary-HeatKV (evicted after its layer), sinks only if naive
+    want = list(range(0, 7)) if variant == binding.VARIANT_BINARY else [0]
+    assert plan.retained(3, 0, 0).tolist() == want

@@ -350,3 +350,178 @@ def test_scale_dependent_greedy_is_not_minimum_cardinality():
     cand = [it for it in sch["G"][k].items() if it not in Gp]
     best = min(r for r in range(len(cand) + 1) for sub in itertools.combinations(cand, r) if max(sizes(sub)) <= B)
     assert best == len(smaller)
+
+
+# --------------------------------------------------------------------------
+# Binary-HeatKV (Alg. 1, binary form; App. A binary CachedTokens) and the Naive policy (Sec. 4.2)
+# --------------------------------------------------------------------------
+
+BINARY_GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "alg1_binary_hand_example.txt")
+
+
+def _load_binary_golden():
+    rec = dict(G={}, E={}, A={}, M={}, NAIVE_E={}, NAIVE_A={}, R={}, N=None)
+    for line in open(BINARY_GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        p = line.split()
+        if p[0] == "N":
+            rec["N"] = [int(x) for x in p[1:]]
+        elif p[0] == "M":
+            rec["M"][int(p[1])] = [int(x) for x in p[2:]]
+        elif p[0] == "R":
+            rec["R"][(int(p[1]), int(p[2]), int(p[3]))] = [int(x) for x in p[5:]]
+        else:
+            rec[p[0]][int(p[1])] = _parse_items(p[2:])
+    return rec
+
+
+def _heads_of(S):
+    """Heads (l, h) of a binary set (the oracle keeps them in slot i = 0)."""
+    return sorted((l, h) for (i, l, h) in S.items() if i == 0)
+
+
+def _pin_binary_hand_example():
+    g = _load_binary_golden()
+    L, H, s, B = 3, 2, 1, 39
+    t = orc.one_based([1, 2, 4, 6, 9])
+    c = orc.cumulative(t)
+    K = 5
+    a, b, c_, d, e, f = (1, 1), (1, 2), (2, 1), (2, 2), (3, 1), (3, 2)
+    order = [d, a, f, c_, b, e]
+    N = orc.heads_to_prune(L * H, t, s, B)
+    assert N[1:] == g["N"]
+    sch = orc.binary_heatkv_schedule(order, N, t, s, L, H, B)
+    for name in "GEA":
+        for k, want in g[name].items():
+            assert _heads_of(sch[name][k]) == want, (name, k)
+    empty = orc._Sets(K, L, H)
+    for k, want in g["M"].items():
+        Gp = sch["G"][k - 1] if k > 1 else empty
+        got = [orc.cache_size_after_layer(k, l, sch["G"][k], Gp, sch["E"][k], t, c, s, L, H, binary=True)
+               for l in range(1, L + 1)]
+        assert got == want, (k, got)
+    for (k, l, h), want in g["R"].items():
+        assert orc.retained_scales(sch["A"][k], k, l, h, s, binary=True) == want
+    nv = orc.binary_heatkv_schedule(order, N, t, s, L, H, B, naive=True)
+    for k, want in g["NAIVE_E"].items():
+        assert _heads_of(nv["E"][k]) == want
+    for k, want in g["NAIVE_A"].items():
+        assert _heads_of(nv["A"][k]) == want
+
+
+def test_hand_worked_example_of_binary_algorithm_1_and_naive_policy():
+    _pin_binary_hand_example()
+
+
+def _binary_random_case(seed, L, H, sides, s, num, den):
+    rng = np.random.default_rng(seed)
+    t = orc.one_based(hi.tokens_per_scale(sides))
+    c = orc.cumulative(t)
+    K, T = len(t) - 1, L * H
+    B = (T * c[K - 1] * num) // den
+    heads = [(l, h) for l in range(1, L + 1) for h in range(1, H + 1)]
+    order = [heads[j] for j in rng.permutation(T)]
+    return t, c, K, T, B, order, orc.heads_to_prune(T, t, s, B)
+
+
+BINARY_CASES = [
+    (0, 3, 4, (1, 2, 3, 4, 5, 6), 2, 1, 2),
+    (1, 4, 2, (1, 2, 4, 6, 8, 12, 16), 3, 1, 4),
+    (2, 2, 8, hi.SIDES_1024, 3, 1, 10),
+    (3, 5, 3, (1, 2, 4, 6, 8, 12), 1, 1, 3),
+    (4, 6, 2, (1, 2, 4, 6, 8, 12, 16, 20), 3, 3, 20),
+]
+
+
+def _pin_binary_totals_and_early_set(seed, L, H, sides, s, num, den, naive):
+    """Sec. 3.2 fixes the cache total at the end of scale k: N_k c_s + (T - N_k) c_k <= B.  Eq. 5 makes N_k
+    minimal, so one head more at c_k instead of c_s would exceed B: a newly pruned head of any layer but the
+    first that were left in the cache would push the total after layer 1 over the budget, and a newly pruned
+    head of layer 1 is already gone in that total.  Hence, for Binary-HeatKV, E_k is exactly the newly pruned
+    heads outside layer 1, and the Alg. 2 total equals the Sec. 3.2 figure after every layer; for the Naive
+    policy E_k is all newly pruned heads and the same total holds."""
+    t, c, K, T, B, order, N = _binary_random_case(seed, L, H, sides, s, num, den)
+    sch = orc.binary_heatkv_schedule(order, N, t, s, L, H, B, naive=naive)
+    empty = orc._Sets(K, L, H)
+    pruned_something = False
+    for k in range(1, K):
+        Gk, Gp = sch["G"][k], (sch["G"][k - 1] if k > 1 else empty)
+        assert _heads_of(Gk) == sorted(order[:N[k]])                      # prefix of the one order
+        fresh = [lh for lh in _heads_of(Gk) if (0,) + lh not in Gp]
+        want_E = fresh if naive else [lh for lh in fresh if lh[0] >= 2]
+        assert _heads_of(sch["E"][k]) == want_E, (k, naive)
+        assert _heads_of(sch["A"][k]) == sorted(set(_heads_of(Gp)) | set(want_E))
+        if k > s:
+            total = N[k] * c[s] + (T - N[k]) * c[k]
+            assert total <= B
+            for layer in range(1, L + 1):
+                got = orc.cache_size_after_layer(k, layer, Gk, Gp, sch["E"][k], t, c, s, L, H, binary=True)
+                assert got == total, (k, layer, got, total)
+        pruned_something |= bool(want_E)
+    assert _heads_of(sch["A"][K]) == _heads_of(sch["G"][K - 1])
+    assert pruned_something
+
+
+@pytest.mark.parametrize("naive", [False, True])
+@pytest.mark.parametrize("seed,L,H,sides,s,num,den", BINARY_CASES)
+def test_binary_cache_total_is_the_sec32_figure_after_every_layer(seed, L, H, sides, s, num, den, naive):
+    _pin_binary_totals_and_early_set(seed, L, H, sides, s, num, den, naive)
+
+
+def _replay_cache(sch, t, s, L, H, B, N, c, binary, check_end_total=True):
+    """Plays a schedule on explicit per-head cache contents (sets of scale indices), independent of the
+    oracle's accounting functions: before scale k the heads (head-scales) of A_k are dropped, after each layer
+    the layer's heads gain scale k unless G_k says otherwise and lose what G_k names.  What a head holds when a
+    scale starts must be what retained_scales reports; the token count never exceeds B (the accounting of
+    Alg. 2 counts layers that have not run as if they already held scale k, so the true count is below it)."""
+    K, T = len(t) - 1, L * H
+    held = {(l, h): set() for l in range(1, L + 1) for h in range(1, H + 1)}
+    gone = (lambda S, i, lh: (0,) + lh in S) if binary else (lambda S, i, lh: (i,) + lh in S)
+    for k in range(1, K + 1):
+        for lh in held:
+            held[lh] = {i for i in held[lh] if i <= s or not gone(sch["A"][k], i, lh)}
+            assert sorted(held[lh]) == orc.retained_scales(sch["A"][k], k, lh[0], lh[1], s, binary=binary)
+        if k == K:
+            break
+        for layer in range(1, L + 1):
+            for h in range(1, H + 1):
+                lh = (layer, h)
+                held[lh].add(k)
+                held[lh] = {i for i in held[lh] if i <= s or not gone(sch["G"][k], i, lh)}
+            assert sum(t[i] for v in held.values() for i in v) <= B
+        if check_end_total and k > s:
+            kept = T * c[k] - sum(t[i] * N[k] for i in range(s + 1, k + 1))
+            assert sum(t[i] for v in held.values() for i in v) == kept
+
+
+@pytest.mark.parametrize("naive", [False, True])
+@pytest.mark.parametrize("seed,L,H,sides,s,num,den", BINARY_CASES)
+def test_binary_schedule_replayed_on_explicit_cache_contents(seed, L, H, sides, s, num, den, naive):
+    t, c, K, T, B, order, N = _binary_random_case(seed, L, H, sides, s, num, den)
+    sch = orc.binary_heatkv_schedule(order, N, t, s, L, H, B, naive=naive)
+    _replay_cache(sch, t, s, L, H, B, N, c, binary=True)
+
+
+@pytest.mark.parametrize("naive", [False, True])
+@pytest.mark.parametrize("seed,L,H,sides,s,num,den", BINARY_CASES[:4])
+def test_scale_dependent_schedule_replayed_on_explicit_cache_contents(seed, L, H, sides, s, num, den, naive):
+    t, c, K, T, B, beta = _random_case(seed, L, H, sides, s, num, den)
+    N = orc.heads_to_prune(T, t, s, B)
+    sch = orc.heatkv_schedule(orc.head_orders(beta, L, H, K, s), N, t, s, L, H, B, naive=naive)
+    _replay_cache(sch, t, s, L, H, B, N, c, binary=False)
+
+
+def test_binary_pins_catch_a_wrong_cached_tokens(monkeypatch):
+    # The pins above are only worth something if a plausible slip in the binary accounting fails them: count
+    # a kept head with c_{k-1} instead of c_k (scale k's own tokens forgotten) and run them again.
+    def forgot_current_scale(k, t, c, s, P):
+        return np.where(P.m[0], c[s], c[k - 1]).astype(np.int64)
+
+    monkeypatch.setattr(orc, "cached_tokens_binary", forgot_current_scale)
+    with pytest.raises(AssertionError):
+        _pin_binary_hand_example()
+    for naive in (False, True):
+        with pytest.raises(AssertionError):
+            _pin_binary_totals_and_early_set(*BINARY_CASES[0], naive)
