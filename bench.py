@@ -7,10 +7,15 @@ the compressed cache followed by the cache append/compaction.  The default
 workload is one Infinity-2B-like layer (16 heads, d=128, bf16, batch 2,
 13 scales = 10521 tokens, 4x budget).
 
-Prints ONE JSON line.  `value` counts the algorithmic FLOPs of the two
-contraction kernels (calibrate QK^T and attend QK^T + PV over the *retained*
-keys) per second of whole-step wall time; `roofline` is the attention kernel
-alone, timed with HIP events on its own stream inside the timed region;
+Prints ONE JSON line.  `value` is the headline metric on the default workload:
+heatkv_attend_scale's algorithmic TFLOP/s (QK^T + PV over the *retained* keys)
+over the 13 launches of a step, timed with HIP events on the launch stream
+inside the timed region; `roofline` is the same kernel against the bf16 MFMA
+peak; `whole_step_tflops` adds the calibration FLOPs and divides by the whole
+step's wall time.  `roofline_hbm` is the metric's second leg, KV GB/s on the
+launches bound by the K/V read (serving stack, batch 32, scales of 36-256
+tokens), `stacks_20x` its third (per-image attention ms at the 20x budget, with
+per-scale TFLOP/s, GB/s and the cache-update kernel's copy bandwidth);
 `cpu_baseline` is the fp64 NumPy oracle on a bounded sample of the same work.
 """
 from __future__ import annotations
@@ -29,9 +34,23 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
-# HBM bytes per attend launch (average over the 13 launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE,
-# scaled by a plain copy of known size; see profiles/attend_layer2b_hbm_traffic.txt.  Other workloads: not measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"layer2b": 37.3e6}
+METRIC = "attend_scale TFLOP/s + KV GB/s (% of MI355X peak); per-image attention ms at 20x"
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "attend_hbm_traffic.txt")
+
+
+def measured_traffic(key):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE, scaled by a plain copy of known size).  The summary carries one line `TRAFFIC <key> <bytes>` per
+    workload it covers; anything else (file missing, workload not profiled) gives None: the figure is never typed
+    into this file, so it cannot outlive the profile it came from."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            p = line.split()
+            if len(p) == 3 and p[0] == "TRAFFIC" and p[1] == key:
+                return float(p[2])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -69,6 +88,7 @@ def main():
 
     import heatkv_inputs as hi
     import paper_2605_14877_amd as hk
+    from paper_2605_14877_amd import probe as hp
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -202,9 +222,8 @@ def main():
     large_tflops = (sum(att_flops[kk] for kk in large) / (sum(att_ms_k[kk] for kk in large) * 1e-3) / 1e12) if large else None
 
     result = {
-        "metric": "attend_scale+calibrate algorithmic TFLOP/s over one hot-path step "
-                  "(calibrate -> schedule -> per-scale attend + append)",
-        "value": round(value, 3),
+        "metric": METRIC,
+        "value": round(att_tflops, 3),
         "unit": "TFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -219,6 +238,9 @@ def main():
                                f"{K} scales ({c[-1]} tokens), {cfg['factor']}x budget, sinks {s}",
                    "attend_only": bool(args.attend_only), "fused_append": not args.separate_append,
                    "calibrate": "per scale" if args.calibrate_per_scale else "all scales in one launch"},
+        "value_is": "heatkv_attend_scale algorithmic TFLOP/s over the 13 launches of a step (HIP events around each "
+                    "launch, fused cache update included unless --separate-append)",
+        "whole_step_tflops": round(value, 3),
         "attend_scale_tflops": round(att_tflops, 2),
         "attend_scale_ms_per_step": round(total_att_ms, 4),
         "attend_pct_of_bf16_peak": round(100 * att_tflops / PEAK_BF16_TFLOPS, 2),
@@ -237,7 +259,7 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+            "traffic": measured_traffic(args.workload),
             "algorithmic_bytes_per_launch": round(sum(att_bytes) / K),
             "flops_per_step": sum(att_flops),
             "launches_per_step": K,
@@ -274,8 +296,9 @@ def mfma_probe(dev):
     import torch
 
     import paper_2605_14877_amd as hk
+    from paper_2605_14877_amd import probe as hp
 
-    nbytes = hk.heatkv_probe_mfma_operand_bytes()
+    nbytes = hp.heatkv_probe_mfma_operand_bytes()
     workgroups, iters = 2048, 2000
     out = torch.empty(workgroups * 256, dtype=torch.float32, device=dev)
     flop = workgroups * 4 * iters * 32 * 32768.0
@@ -291,7 +314,7 @@ def mfma_probe(dev):
         for _ in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            hk.heatkv_probe_mfma(ops, out, workgroups, iters)
+            hp.heatkv_probe_mfma(ops, out, workgroups, iters)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1)
@@ -299,14 +322,14 @@ def mfma_probe(dev):
         res[name] = round(flop / best / 1e9, 1)
     # the attention kernel's tile step without its bookkeeping (same instruction mix, dependencies, LDS tiles,
     # barrier and tile copies, random bf16 tiles served from L2): what that mix sustains on this GPU
-    tiles = torch.randn(hk.heatkv_probe_tile_step_bytes() // 2, device=dev, generator=g).to(torch.bfloat16)
+    tiles = torch.randn(hp.heatkv_probe_tile_step_bytes() // 2, device=dev, generator=g).to(torch.bfloat16)
     t_iters = 600
     out2 = torch.empty(workgroups * 256, dtype=torch.float32, device=dev)
     best = None
     for _ in range(3):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        hk.heatkv_probe_tile_step(tiles, out2, workgroups, t_iters)
+        hp.heatkv_probe_tile_step(tiles, out2, workgroups, t_iters)
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1)
@@ -323,9 +346,10 @@ def hbm_read_probe(dev):
     import torch
 
     import paper_2605_14877_amd as hk
+    from paper_2605_14877_amd import probe as hp
 
     wgs = 1024
-    src = torch.empty(hk.heatkv_probe_tile_stream_bytes(wgs, 64), dtype=torch.uint8, device=dev)
+    src = torch.empty(hp.heatkv_probe_tile_stream_bytes(wgs, 64), dtype=torch.uint8, device=dev)
     src.random_(0, 256)
     out = torch.empty(wgs * 256, dtype=torch.int32, device=dev)
     res = {"unit": "GB/s", "workgroups": wgs}
@@ -336,12 +360,12 @@ def hbm_read_probe(dev):
             part = src[i * offset_steps * wgs * 32768:]
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            hk.heatkv_probe_tile_stream(part, out, wgs, steps)
+            hp.heatkv_probe_tile_stream(part, out, wgs, steps)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1)
             best = ms if best is None else min(best, ms)
-        return round(hk.heatkv_probe_tile_stream_bytes(wgs, steps) / best / 1e6, 1)
+        return round(hp.heatkv_probe_tile_stream_bytes(wgs, steps) / best / 1e6, 1)
 
     res["walk_64_steps"] = best_of(4, 64, 0)
     res["walk_9_steps"] = best_of(6, 9, 9)  # six disjoint 288 MiB parts of the buffer, none read twice in a row
@@ -380,6 +404,7 @@ def stack_result(args, dev):
 
     import heatkv_inputs as hi
     import paper_2605_14877_amd as hk
+    from paper_2605_14877_amd import probe as hp
 
     cfg = hi.CONFIGS[args.workload]
     t0 = hi.tokens_per_scale(cfg["sides"])

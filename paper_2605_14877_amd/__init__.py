@@ -24,12 +24,6 @@ from .binding import (  # noqa: F401
     heatkv_calibrate_scales_accumulate,
     heatkv_head_scores,
     heatkv_load_schedule,
-    heatkv_probe_mfma,
     heatkv_rank_dispersion,
-    heatkv_probe_mfma_operand_bytes,
-    heatkv_probe_tile_step,
-    heatkv_probe_tile_step_bytes,
-    heatkv_probe_tile_stream,
-    heatkv_probe_tile_stream_bytes,
     library_path,
 )

@@ -63,10 +63,6 @@ def lib():
     L.heatkv_calibrate_scales_accumulate.restype = C.c_int
     L.heatkv_calibrate_scales_accumulate.argtypes = [sp, C.c_int, C.c_int, i32p, C.POINTER(vp), C.POINTER(vp),
                                                      C.c_float, C.c_float, vp, C.POINTER(vp), vp, C.c_size_t, vp]
-    L.heatkv_probe_tile_stream_bytes.restype = C.c_size_t
-    L.heatkv_probe_tile_stream_bytes.argtypes = [C.c_int, C.c_int]
-    L.heatkv_probe_tile_stream.restype = C.c_int
-    L.heatkv_probe_tile_stream.argtypes = [vp, C.c_size_t, vp, C.c_int, C.c_int, vp]
     L.heatkv_accumulate_beta.restype = C.c_int
     L.heatkv_accumulate_beta.argtypes = [sp, C.c_int, C.c_int, vp, C.c_float, vp, vp]
     L.heatkv_build_schedule.restype = C.c_int
@@ -108,14 +104,6 @@ def lib():
     L.heatkv_head_scores.argtypes = [sp, f32p, C.c_int, C.c_int, f64p]
     L.heatkv_rank_dispersion.restype = C.c_int
     L.heatkv_rank_dispersion.argtypes = [sp, f32p, C.c_int, C.c_int, C.c_int, f64p]
-    L.heatkv_probe_mfma_operand_bytes.restype = C.c_size_t
-    L.heatkv_probe_mfma_operand_bytes.argtypes = []
-    L.heatkv_probe_mfma.restype = C.c_int
-    L.heatkv_probe_mfma.argtypes = [vp, vp, C.c_int, C.c_int, vp]
-    L.heatkv_probe_tile_step_bytes.restype = C.c_size_t
-    L.heatkv_probe_tile_step_bytes.argtypes = []
-    L.heatkv_probe_tile_step.restype = C.c_int
-    L.heatkv_probe_tile_step.argtypes = [vp, vp, C.c_int, C.c_int, vp]
     _lib = L
     return L
 
@@ -374,31 +362,6 @@ def heatkv_calibrate_scales_accumulate(shape, layer, k1_list, q_list, k_all_list
                                                     _stream() if stream is None else stream))
 
 
-def heatkv_probe_tile_stream_bytes(workgroups, steps):
-    return int(lib().heatkv_probe_tile_stream_bytes(int(workgroups), int(steps)))
-
-
-def heatkv_probe_tile_stream(src, out, workgroups, steps, stream=None):
-    """Measurement aid: the attention kernel's HBM -> LDS tile copies without arithmetic (see include/heatkv.h)."""
-    _check_tensor(src, "src")
-    _check_tensor(out, "out", min_bytes=max(int(workgroups), 0) * 256 * 4)
-    src_bytes = 0 if src is None else src.numel() * src.element_size()
-    _check(lib().heatkv_probe_tile_stream(_ptr(src), src_bytes, _ptr(out), int(workgroups), int(steps),
-                                          _stream() if stream is None else stream))
-
-
-def heatkv_probe_mfma_operand_bytes():
-    return int(lib().heatkv_probe_mfma_operand_bytes())
-
-
-def heatkv_probe_mfma(operands, out, workgroups, iters, stream=None):
-    """Measurement aid: back-to-back bf16 MFMAs on the caller's operand bits (see include/heatkv.h)."""
-    _check_tensor(operands, "operands", min_bytes=heatkv_probe_mfma_operand_bytes())
-    _check_tensor(out, "out", min_bytes=max(int(workgroups), 0) * 256 * 4)
-    _check(lib().heatkv_probe_mfma(_ptr(operands), _ptr(out), int(workgroups), int(iters),
-                                   _stream() if stream is None else stream))
-
-
 def heatkv_head_scores(shape, beta, sinks, variant=VARIANT_HEATKV):
     """[K][T] fp64 scores behind the orders (Eq. 3 / Eq. 4 sums); beta: host [L,H,K,K] float32."""
     beta = np.ascontiguousarray(beta, dtype=np.float32)
@@ -415,15 +378,3 @@ def heatkv_rank_dispersion(shape, betas, sinks, variant=VARIANT_HEATKV):
     _check(lib().heatkv_rank_dispersion(shape.ref, betas.ctypes.data_as(C.POINTER(C.c_float)), int(betas.shape[0]),
                                         int(sinks), int(variant), out.ctypes.data_as(C.POINTER(C.c_double))))
     return out
-
-
-def heatkv_probe_tile_step_bytes():
-    return int(lib().heatkv_probe_tile_step_bytes())
-
-
-def heatkv_probe_tile_step(tiles, out, workgroups, iters, stream=None):
-    """Measurement aid: a model of the bf16 attention kernel's tile step (see include/heatkv.h)."""
-    _check_tensor(tiles, "tiles", min_bytes=heatkv_probe_tile_step_bytes())
-    _check_tensor(out, "out", min_bytes=max(int(workgroups), 0) * 256 * 4)
-    _check(lib().heatkv_probe_tile_step(_ptr(tiles), _ptr(out), int(workgroups), int(iters),
-                                        _stream() if stream is None else stream))

@@ -1,4 +1,5 @@
-"""Builds libheatkv.so (HIP kernels + host planner + C ABI) for gfx950 with hipcc."""
+"""Builds the two shared libraries for gfx950 with hipcc: libheatkv.so (HIP kernels + host planner + C ABI of
+include/heatkv.h) and libheatkv_probe.so (the measurement aids of include/heatkv_probe.h, for bench.py)."""
 from __future__ import annotations
 
 import os
@@ -9,7 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheatkv.so")
-SOURCES = ["plan.cpp", "abi.cpp", "attend.hip", "append.hip", "calibrate.hip", "probe.hip"]
+PROBE_LIB = os.path.join(HERE, "libheatkv_probe.so")
+LIBRARIES = {LIB: ["plan.cpp", "abi.cpp", "attend.hip", "append.hip", "calibrate.hip"], PROBE_LIB: ["probe.hip"]}
+SOURCES = [src for srcs in LIBRARIES.values() for src in srcs]
 
 # Packed-fp32 VALU forms are switched off for every device translation unit.
 HIP_FLAGS = [
@@ -42,10 +45,12 @@ def build(verbose: bool = True) -> str:
             print(f"compile failed: {src}", file=sys.stderr)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    for lib, srcs in LIBRARIES.items():
+        cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib,
+               *[os.path.join(HERE, "_build", src + ".o") for src in srcs]]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return LIB
 
 

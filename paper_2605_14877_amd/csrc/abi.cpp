@@ -459,40 +459,4 @@ int heatkv_rank_dispersion(const heatkv_shape* shape, const float* betas, int ru
   }
 }
 
-size_t heatkv_probe_mfma_operand_bytes(void) { return heatkv::probe_mfma_operand_bytes(); }
-
-int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iters, void* stream) {
-  if (!operands || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
-  if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20)) return fail(HEATKV_EINVAL, "probe size out of range");
-  hipError_t e = heatkv::launch_probe_mfma(operands, out, workgroups, iters, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(e, "probe_mfma launch");
-  return HEATKV_OK;
-}
-
-size_t heatkv_probe_tile_step_bytes(void) { return heatkv::probe_tile_step_bytes(); }
-
-int heatkv_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, void* stream) {
-  if (!tiles || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
-  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || (iters & 1))
-    return fail(HEATKV_EINVAL, "probe size out of range (iters must be even)");
-  hipError_t e = heatkv::launch_probe_tile_step(tiles, out, workgroups, iters, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(e, "probe_tile_step launch");
-  return HEATKV_OK;
-}
-
-size_t heatkv_probe_tile_stream_bytes(int workgroups, int steps) {
-  if (workgroups <= 0 || workgroups > (1 << 20) || steps <= 0 || steps > (1 << 20)) return 0;
-  return heatkv::probe_tile_stream_bytes(workgroups, steps);
-}
-
-int heatkv_probe_tile_stream(const void* src, size_t src_bytes, uint32_t* out, int workgroups, int steps, void* stream) {
-  if (!src || !out) return fail(HEATKV_EINVAL, "null tensor pointer");
-  const size_t need = heatkv_probe_tile_stream_bytes(workgroups, steps);
-  if (need == 0) return fail(HEATKV_EINVAL, "probe size out of range");
-  if (src_bytes < need) return fail(HEATKV_EINVAL, "probe source smaller than workgroups x steps x 32 KB");
-  hipError_t e = heatkv::launch_probe_tile_stream(src, out, workgroups, steps, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(e, "probe_tile_stream launch");
-  return HEATKV_OK;
-}
-
 }  // extern "C"

@@ -13,6 +13,7 @@
 #include "copy_rows.h"
 #include "device_util.h"
 #include "kernels.h"
+#include "tile_lds.h"
 
 namespace heatkv {
 
@@ -49,7 +50,8 @@ struct AttendParams {
 // stored row-major, 256 bytes per row, unpadded; the 16-byte chunks of a row are
 // XOR-swizzled with the row number (the lane that fills an LDS slot simply
 // fetches the matching global chunk), K tiles and V tiles each with the pattern
-// that keeps their read instruction free of bank conflicts.
+// that keeps their read instruction free of bank conflicts (tile_lds.h holds the
+// format; the calibration kernel and the measurement probes share it).
 //
 // Scores are produced transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: K
 // rows are the A operand straight from LDS, Q stays in registers as the B operand.
@@ -60,21 +62,10 @@ struct AttendParams {
 // inside a 16-key MFMA step is permuted identically on both operands.
 // ---------------------------------------------------------------------------
 constexpr int BM = 128;              // queries per workgroup
-constexpr int BN = 64;               // keys per tile
+constexpr int BN = tile::ROWS;       // keys per tile
 constexpr int D128 = 128;
-constexpr int ROW_BYTES = 256;       // one bf16 row
-constexpr int TILE_BYTES = BN * ROW_BYTES;
-
-// Chunk swizzles.  The LDS has 64 four-byte banks (256 bytes per clock).
-// K tiles: ds_read_b128 serves 16 consecutive lanes per clock; they read the same logical chunk of 16
-// consecutive rows, so the chunk is XORed with row % 16 and the 16 accesses cover all 64 banks (measured
-// 246 bytes/clock per compute unit against 128 with an 8-row pattern).
-// V tiles: the transposing 8-byte read serves 32 lanes per clock, a block of 4 rows x 64 bytes; XORing the
-// 64-byte window index (chunk bits 2-3) with row % 4 puts the four rows on four different bank quarters
-// (measured 156-162 bytes/clock, the instruction's ceiling, against 125).
-// Both depend only on row % 16, so they are the same for the four rows a lane loads in one tile (16 apart).
-__device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
-__device__ __forceinline__ int swizzle_v(int row) { return (row & 3) << 2; }
+constexpr int ROW_BYTES = tile::ROW_BYTES;
+constexpr int TILE_BYTES = tile::BYTES;
 
 extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 
@@ -142,33 +133,17 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   const int steps_all = (tiles_all + KS - 1) / KS;
   auto has_tile = [&](int j) { return KS == 1 || KS * j + g < tiles_all; };
 
-  // Loader: wavefront w fills LDS bytes [(4j + w) KB, +1 KB) of a tile with instruction j = 0..3, lane L
-  // lands on byte 16 L of that range, i.e. row 4 (4j + w) + L / 16 = ld_row0 + 16 j, slot L % 16.  The
-  // swizzle is the same for all j, so one per-lane offset serves the four instructions (the 4 KB step
-  // between them goes into the scalar base address).
-  const int ld_row0 = 4 * wave + (lane >> 4);
-  const int ld_off_k = ld_row0 * ROW_BYTES + (((lane & 15) ^ swizzle_k(ld_row0)) << 4);
-  const int ld_off_v = ld_row0 * ROW_BYTES + (((lane & 15) ^ swizzle_v(ld_row0)) << 4);
-  // The copy HBM -> LDS is issued as raw global_load_lds instructions (issue_k / issue_v below): the
-  // compiler then does not see an LDS store it would have to order against the tile reads of the other
-  // buffer (it would wait for the whole prefetch in the middle of the math).  Ordering is explicit
-  // instead: s_waitcnt vmcnt(0) and the workgroup barrier at the top of every tile step.
+  // Loader and reader offsets of the shared tile format.  The copy HBM -> LDS is issued as raw global_load_lds
+  // instructions (tile::issue_full / issue_ragged): the compiler then does not see an LDS store it would have to
+  // order against the tile reads of the other buffer (it would wait for the whole prefetch in the middle of the
+  // math).  Ordering is explicit instead: s_waitcnt vmcnt(0) and the workgroup barrier at the top of every step.
+  const int ld_off_k = tile::loader_off_k(wave, lane);
+  const int ld_off_v = tile::loader_off_v(wave, lane);
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<unsigned long long>(
       (__attribute__((address_space(3))) char*)(&lds[0][0][0]))) + g * (4 * TILE_BYTES);
-  // Reader offsets inside a tile.
-  int k_off[8];  // K operand: row n (+32 cb), chunk 2 ks + hl
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * ROW_BYTES + (((2 * ks + hl) ^ swizzle_k(n)) << 4);
-  // V operand through the transposing read: lane i of a 16-lane group points at row key0 + 4 hl + i / 4,
-  // columns 32 dblk + 16 (group & 1) + 4 (i % 4) .. +3, and receives column i of that 4 x 16 block.
-  const int tr_i = lane & 15, tr_grp = lane >> 4;
-  const int v_row = 4 * hl + (tr_i >> 2);
-  int v_off[4];
-#pragma unroll
-  for (int dblk = 0; dblk < 4; ++dblk) {
-    const int chunk = 4 * dblk + 2 * (tr_grp & 1) + ((tr_i & 3) >> 1);
-    v_off[dblk] = v_row * ROW_BYTES + ((chunk ^ swizzle_v(v_row)) << 4) + ((tr_i & 1) << 3);
-  }
+  int k_off[8], v_off[4];
+  tile::reader_off_k(lane, k_off);
+  tile::reader_off_v(lane, v_off);
 
   f32x16 o[4];
 #pragma unroll
@@ -195,26 +170,12 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
     const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
-    const unsigned kd = lds_base + buf * (2 * TILE_BYTES) + wave * 1024;
-    // Two separate statements under a workgroup-uniform branch: the full-tile path has no per-lane arithmetic at
-    // all.  (The comment inside the ragged variant's text keeps the two from being merged back into one
-    // statement with per-lane selected operands, 24 vector instructions in every step.)
-    if (left >= BN) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd + j * 4096), "v"(ld_off_k),
-                     "s"(kb + j * (16 * ROW_BYTES))
-                     : "memory");
-    } else {  // ragged tile: rows past the end re-read the last valid row
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = ld_row0 + 16 * j;
-        const int rr = row < left ? row : left - 1;
-        const int off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_k(row)) << 4);
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t; ragged" ::"s"(kd + j * 4096), "v"(off), "s"(kb)
-                     : "memory");
-      }
-    }
+    const unsigned kd = lds_base + buf * (2 * TILE_BYTES);
+    // Two separate statements under a workgroup-uniform branch: the full-tile path has no per-lane arithmetic.
+    if (left >= BN)
+      tile::issue_full(kd, wave, ld_off_k, kb);
+    else
+      tile::issue_ragged<false>(kd, wave, lane, left, kb);
   };
   auto issue_v = [&](int j, int buf) {
     const int it = KS * j + g;
@@ -222,23 +183,11 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
-    const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES + wave * 1024;
-    if (left >= BN) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(vd + j * 4096), "v"(ld_off_v),
-                     "s"(vb + j * (16 * ROW_BYTES))
-                     : "memory");
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = ld_row0 + 16 * j;
-        const int rr = row < left ? row : left - 1;
-        const int off = rr * ROW_BYTES + (((lane & 15) ^ swizzle_v(row)) << 4);
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t; ragged" ::"s"(vd + j * 4096), "v"(off), "s"(vb)
-                     : "memory");
-      }
-    }
+    const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES;
+    if (left >= BN)
+      tile::issue_full(vd, wave, ld_off_v, vb);
+    else
+      tile::issue_ragged<true>(vd, wave, lane, left, vb);
   };
 
   // S^T = K Q^T for the 64 keys of the K tile in buffer `buf` x this wavefront's 32 queries.

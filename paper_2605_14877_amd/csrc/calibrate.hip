@@ -17,6 +17,7 @@
 
 #include "device_util.h"
 #include "kernels.h"
+#include "tile_lds.h"
 
 namespace heatkv {
 
@@ -67,14 +68,10 @@ __device__ __forceinline__ int scale_of_block(const CalibParams& p, int block) {
 // longer workgroups and ends with a shorter tail.
 // ---------------------------------------------------------------------------
 constexpr int CBM1 = 128;  // queries per set of four wavefronts
-constexpr int CBN = 64;
+constexpr int CBN = tile::ROWS;
 constexpr int CD = 128;
-constexpr int CROW_BYTES = 256;
-constexpr int CTILE_BYTES = CBN * CROW_BYTES;
-
-// Chunk swizzle of a K tile: ds_read_b128 serves 16 consecutive lanes per clock, which read one logical chunk
-// of 16 consecutive rows; XORing the chunk with row % 16 spreads them over all 64 LDS banks.
-__device__ __forceinline__ int swizzle_k(int row) { return row & 15; }
+constexpr int CROW_BYTES = tile::ROW_BYTES;
+constexpr int CTILE_BYTES = tile::BYTES;
 
 // Dynamic LDS: two K tiles, then blk_sum[k1+1][rows], blk_max[k1+1][rows], fin_max[rows] (floats), rows = the
 // queries of a workgroup.
@@ -120,33 +117,22 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
   }
   const float c = p.sm_scale * kLog2e;
 
-  // HBM -> LDS copy of one tile (see the attention kernel: raw global_load_lds, explicit ordering).
-  // Instruction j of wavefront w fills rows ld_row0 + 16 j; the swizzle depends on row % 16 only, so one
-  // per-lane offset serves all four (the 4 KB step goes into the scalar base address).
-  const int ld_row0 = 4 * wave + (lane >> 4);
-  const int ld_off = ld_row0 * CROW_BYTES + (((lane & 15) ^ swizzle_k(ld_row0)) << 4);
+  // HBM -> LDS copy of one K tile in the tile format shared with the attention kernel (tile_lds.h: raw
+  // global_load_lds, explicit ordering by s_waitcnt vmcnt + barrier).
+  const int ld_off = tile::loader_off_k(wave, lane);
   const unsigned lds_base =
       static_cast<unsigned>(reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0])));
-  auto issue_tile = [&](int k2, int tile, int buf) {
-    const int left = p.t[k2] - tile * CBN;
-    const char* kb = kbase + static_cast<long long>(p.c[k2] - p.t[k2] + tile * CBN) * CROW_BYTES;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int off = ld_off;
-      const char* src = kb + j * (16 * CROW_BYTES);
-      if (left < CBN) {  // ragged tile: rows past the end re-read the last valid row
-        const int row = ld_row0 + 16 * j;
-        const int rr = row < left ? row : left - 1;
-        off = rr * CROW_BYTES + (((lane & 15) ^ swizzle_k(row)) << 4);
-        src = kb;
-      }
-      const unsigned kd = lds_base + buf * CTILE_BYTES + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(kd), "v"(off), "s"(src) : "memory");
-    }
+  auto issue_tile = [&](int k2, int tile_i, int buf) {
+    const int left = p.t[k2] - tile_i * CBN;
+    const char* kb = kbase + static_cast<long long>(p.c[k2] - p.t[k2] + tile_i * CBN) * CROW_BYTES;
+    const unsigned kd = lds_base + buf * CTILE_BYTES;
+    if (left >= CBN)
+      tile::issue_full(kd, wave, ld_off, kb);
+    else  // ragged tile: rows past the end re-read the last valid row
+      tile::issue_ragged<false>(kd, wave, lane, left, kb);
   };
   int k_off[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * CROW_BYTES + (((2 * ks + hl) ^ swizzle_k(n)) << 4);
+  tile::reader_off_k(lane, k_off);
 
   float m_run[CSETS], cur[CSETS];
 #pragma unroll

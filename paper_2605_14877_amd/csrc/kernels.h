@@ -68,20 +68,8 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);
 hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
                                   float* beta, hipStream_t stream);
 
-// Matrix-core probe: `workgroups` x 4 wavefronts each issue iters x 32 independent 32x32x16 bf16 MFMAs on
-// operands taken from `operands` (probe_mfma_operand_bytes() bytes); out receives workgroups x 256 floats.
-// Tile stream: `workgroups` x 256 threads each copy `steps` consecutive 32 KB steps of src into LDS the way the
-// attention kernel does, no arithmetic; out receives workgroups x 256 checksum words.
-size_t probe_tile_stream_bytes(int workgroups, int steps);
-hipError_t launch_probe_tile_stream(const void* src, unsigned* out, int workgroups, int steps, hipStream_t stream);
 // One-time set-up of the attention kernels on the current device (the LDS limit of the two-stream instance);
 // called at plan upload, repeated calls are cheap.
 hipError_t attend_prepare_device();
-size_t probe_mfma_operand_bytes();
-hipError_t launch_probe_mfma(const void* operands, float* out, int workgroups, int iters, hipStream_t stream);
-// Tile-step model of the bf16 attention kernel: `workgroups` x 4 wavefronts each run `iters` (even) model steps of
-// 32 MFMAs on the probe_tile_step_bytes() bytes of bf16 tile data in `tiles`; out receives workgroups x 256 floats.
-size_t probe_tile_step_bytes();
-hipError_t launch_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, hipStream_t stream);
 
 }  // namespace heatkv

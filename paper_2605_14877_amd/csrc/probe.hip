@@ -2,14 +2,19 @@
 // calibration kernels are priced against the datasheet peak; this loop of back-to-back, independent
 // v_mfma_f32_32x32x16_bf16 instructions (no memory traffic, no vector ALU work) shows what the same matrix
 // pipes deliver on the machine at hand, which depends on the operand data through the power-limited clock.
+//
+// This file is all of libheatkv_probe.so (C ABI in include/heatkv_probe.h); nothing here is linked into the
+// product library.  It shares the LDS tile format of the product kernels (tile_lds.h), nothing else.
+#include <string>
 #include <type_traits>
 
+#include <hip/hip_runtime_api.h>
+
 #include "device_util.h"
-#include "kernels.h"
+#include "heatkv_probe.h"
+#include "tile_lds.h"
 
 namespace heatkv {
-
-namespace {
 
 constexpr int kProbeOperands = 4096;  // 16-byte operand slots the kernel reads (64 KB)
 
@@ -53,16 +58,12 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint4* ops, float
 // stay in L2).  Its throughput is what this mix sustains on the chip at hand; the numbers it computes mean
 // nothing.  Two workgroups of four wavefronts per compute unit, as in the kernel.
 // ---------------------------------------------------------------------------
-constexpr int kRowBytes = 256, kTileBytes = 64 * 256, kModelTiles = 64;
-
-__device__ __forceinline__ int model_swizzle_k(int row) { return row & 15; }
-__device__ __forceinline__ int model_swizzle_v(int row) { return (row & 3) << 2; }
+constexpr int kRowBytes = tile::ROW_BYTES, kTileBytes = tile::BYTES, kModelTiles = 64;
 
 __global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv, float* out, int iters) {
   __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = lane & 31, hl = lane >> 5;
   for (int i = tid; i < 4 * kTileBytes / 4; i += 256)
     reinterpret_cast<unsigned*>(&lds[0][0][0])[i] = reinterpret_cast<const unsigned*>(kv)[i];
   __syncthreads();
@@ -77,33 +78,18 @@ __global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv,
     t.u = reinterpret_cast<const uint4*>(kv)[(lane * 8 + i) & 1023];
     qreg[i] = t.v;
   }
-  int k_off[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * kRowBytes + (((2 * ks + hl) ^ model_swizzle_k(n)) << 4);
-  const int tr_i = lane & 15, tr_grp = lane >> 4;
-  const int v_row = 4 * hl + (tr_i >> 2);
-  int v_off[4];
-#pragma unroll
-  for (int dblk = 0; dblk < 4; ++dblk) {
-    const int chunk = 4 * dblk + 2 * (tr_grp & 1) + ((tr_i & 3) >> 1);
-    v_off[dblk] = v_row * kRowBytes + ((chunk ^ model_swizzle_v(v_row)) << 4) + ((tr_i & 1) << 3);
-  }
-  const int ld_row0 = 4 * wave + (lane >> 4);
-  const int ld_off_k = ld_row0 * kRowBytes + (((lane & 15) ^ model_swizzle_k(ld_row0)) << 4);
-  const int ld_off_v = ld_row0 * kRowBytes + (((lane & 15) ^ model_swizzle_v(ld_row0)) << 4);
+  int k_off[8], v_off[4];
+  tile::reader_off_k(lane, k_off);
+  tile::reader_off_v(lane, v_off);
+  const int ld_off_k = tile::loader_off_k(wave, lane);
+  const int ld_off_v = tile::loader_off_v(wave, lane);
   const unsigned lds_base = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(
       reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0][0][0]))));
   // Copy of model tile `tile` (K: which = 0, V: which = 1) into buffer `buf`; all addresses stay inside the
   // 2 * kModelTiles tiles of `kv` and inside the 64 KB of LDS.
-  auto issue = [&](int tile, int buf, int which) {
-    const char* src = kv + (which * kModelTiles + (tile & (kModelTiles - 1))) * kTileBytes;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const unsigned dst = lds_base + buf * (2 * kTileBytes) + which * kTileBytes + (4 * j + wave) * 1024;
-      const char* sj = src + j * 4096;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(which ? ld_off_v : ld_off_k), "s"(sj)
-                   : "memory");
-    }
+  auto issue = [&](int tile_i, int buf, int which) {
+    const char* src = kv + (which * kModelTiles + (tile_i & (kModelTiles - 1))) * kTileBytes;
+    tile::issue_full(lds_base + buf * (2 * kTileBytes) + which * kTileBytes, wave, which ? ld_off_v : ld_off_k, src);
   };
   f32x16 o[4], s_cur[2], s_nxt[2];
 #pragma unroll
@@ -205,11 +191,8 @@ __global__ __launch_bounds__(256, 2) void probe_tile_stream_kernel(const char* s
   auto issue = [&](int t) {
     const char* s = base + static_cast<size_t>(t) * (2 * kTileBytes);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const unsigned dst = lds_base + (t & 1) * (2 * kTileBytes) + (4 * j + wave) * 1024;
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(s + (4 * j + wave) * 1024)
-                   : "memory");
-    }
+    for (int j = 0; j < 8; ++j)
+      tile::copy_1k(lds_base + (t & 1) * (2 * kTileBytes) + (4 * j + wave) * 1024, off, s + (4 * j + wave) * 1024);
   };
   issue(0);
   unsigned acc = 0;
@@ -223,32 +206,63 @@ __global__ __launch_bounds__(256, 2) void probe_tile_stream_kernel(const char* s
   out[blockIdx.x * 256 + tid] = acc;
 }
 
+}  // namespace heatkv
+
+namespace {
+
+constexpr int kOk = 0, kEinval = -1, kEhip = -4;  // the HEATKV_* codes of heatkv.h
+thread_local std::string g_probe_error;
+
+int probe_fail(int code, const std::string& msg) {
+  g_probe_error = msg;
+  return code;
+}
+int probe_launch_result(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return probe_fail(kEhip, std::string(what) + ": " + hipGetErrorString(e));
+  return kOk;
+}
+
 }  // namespace
 
-size_t probe_tile_stream_bytes(int workgroups, int steps) {
-  return size_t(workgroups) * size_t(steps) * (2 * kTileBytes);
+extern "C" {
+
+const char* heatkv_probe_last_error(void) { return g_probe_error.c_str(); }
+
+size_t heatkv_probe_mfma_operand_bytes(void) { return size_t(heatkv::kProbeOperands) * 16; }
+
+int heatkv_probe_mfma(const void* operands, float* out, int workgroups, int iters, void* stream) {
+  if (!operands || !out) return probe_fail(kEinval, "null tensor pointer");
+  if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20)) return probe_fail(kEinval, "probe size out of range");
+  hipLaunchKernelGGL(heatkv::probe_mfma_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(operands), out, iters);
+  return probe_launch_result("probe_mfma launch");
 }
 
-hipError_t launch_probe_tile_stream(const void* src, unsigned* out, int workgroups, int steps, hipStream_t stream) {
-  hipLaunchKernelGGL(probe_tile_stream_kernel, dim3(workgroups), dim3(256), 0, stream, static_cast<const char*>(src),
-                     steps, out);
-  return hipGetLastError();
+size_t heatkv_probe_tile_step_bytes(void) { return size_t(2) * heatkv::kModelTiles * heatkv::kTileBytes; }
+
+int heatkv_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, void* stream) {
+  if (!tiles || !out) return probe_fail(kEinval, "null tensor pointer");
+  if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || (iters & 1))
+    return probe_fail(kEinval, "probe size out of range (iters must be even)");
+  hipLaunchKernelGGL(heatkv::probe_tile_step_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(tiles), out, iters);
+  return probe_launch_result("probe_tile_step launch");
 }
 
-size_t probe_tile_step_bytes() { return size_t(2) * kModelTiles * kTileBytes; }
-
-hipError_t launch_probe_tile_step(const void* tiles, float* out, int workgroups, int iters, hipStream_t stream) {
-  hipLaunchKernelGGL(probe_tile_step_kernel, dim3(workgroups), dim3(256), 0, stream, static_cast<const char*>(tiles), out,
-                     iters);
-  return hipGetLastError();
+size_t heatkv_probe_tile_stream_bytes(int workgroups, int steps) {
+  if (workgroups <= 0 || workgroups > (1 << 20) || steps <= 0 || steps > (1 << 20)) return 0;
+  return size_t(workgroups) * size_t(steps) * (2 * heatkv::kTileBytes);
 }
 
-size_t probe_mfma_operand_bytes() { return size_t(kProbeOperands) * 16; }
-
-hipError_t launch_probe_mfma(const void* operands, float* out, int workgroups, int iters, hipStream_t stream) {
-  hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, stream, static_cast<const uint4*>(operands), out,
-                     iters);
-  return hipGetLastError();
+int heatkv_probe_tile_stream(const void* src, size_t src_bytes, uint32_t* out, int workgroups, int steps, void* stream) {
+  if (!src || !out) return probe_fail(kEinval, "null tensor pointer");
+  const size_t need = heatkv_probe_tile_stream_bytes(workgroups, steps);
+  if (need == 0) return probe_fail(kEinval, "probe size out of range");
+  if (src_bytes < need) return probe_fail(kEinval, "probe source smaller than workgroups x steps x 32 KB");
+  hipLaunchKernelGGL(heatkv::probe_tile_stream_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(src), steps, out);
+  return probe_launch_result("probe_tile_stream launch");
 }
 
-}  // namespace heatkv
+}  // extern "C"

@@ -9,6 +9,7 @@ import torch
 
 import heatkv_inputs as hi
 import paper_2605_14877_amd as hk
+from paper_2605_14877_amd import probe as hp
 from oracle import heatkv_oracle as orc
 from tests import harness
 from tests.gpu_driver import device_generation, oracle_rows
@@ -142,6 +143,72 @@ def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None, fused=False):
         for a, b in zip(outs, outs_sep):
             assert torch.equal(a, b)
     return _check_all(outs, q, k, v, t0, ref["present"], 0, sm, TOL["bf16"], sample_from=sample_from)
+
+
+def _generation_all_layers(plan, dq, t0, sm, fused_layers=()):
+    """Generation order over a whole stack: scale outer, layer inner, one shared pair of arenas.
+    dq[l] = (q, k, v) device tensors of layer l.  Returns outs[l][k]."""
+    c = hi.cumulative_tokens(t0)
+    K, L = len(t0), len(dq)
+    nbytes = max(plan.arena_bytes, 16)
+    ka = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    va = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    outs = [[None] * K for _ in range(L)]
+    for kk in range(K):
+        sl = slice(c[kk] - t0[kk], c[kk])
+        for l in range(L):
+            qk, kc, vc = (x[:, :, sl].contiguous() for x in dq[l])
+            out = torch.empty_like(qk)
+            if l in fused_layers:
+                hk.heatkv_attend_append_scale(plan, l, kk, qk, kc, vc, ka, va, sm, out)
+            else:
+                hk.heatkv_attend_scale(plan, l, kk, qk, kc, vc, ka, va, sm, out)
+                hk.heatkv_append_scale(plan, l, kk, kc, vc, ka, va)
+            outs[l][kk] = out
+    torch.cuda.synchronize()
+    return outs
+
+
+@pytest.mark.parametrize("variant", [hk.VARIANT_BINARY, hk.VARIANT_NAIVE, hk.VARIANT_BINARY_NAIVE])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_generation_under_binary_and_naive_plans(variant, dtype, d):
+    # Alg. 1's binary path (one CAS order, a head keeps all or only the sinks), the Naive policy of Sec. 4.2
+    # (E_k = G_k minus G_{k-1}) and both together: three layers in generation order over one arena, every
+    # (layer, batch row, head, scale, query row) against the oracle's attention over the oracle's retained
+    # scales for that variant.  The budget is tight enough that every variant prunes early somewhere.
+    L, H, s, batch = 3, 4, 2, 2
+    sides = (1, 2, 4, 6, 9, 12, 17) if dtype == "bf16" else (1, 2, 4, 6, 9, 11)
+    t0 = hi.tokens_per_scale(sides)
+    c = hi.cumulative_tokens(t0)
+    K = len(t0)
+    sm = 1.0 / np.sqrt(d)
+    esz = hi.elem_bytes(dtype)
+    cfg = dict(L=L, H=H, d=d, dtype=dtype, batch=batch, sides=sides)
+    B = (L * H * c[-2] * 2) // 5
+    w = hi.head_weights(40 + variant, L, H, K)
+    beta0 = hi.expected_beta_from_weights(w, t0).astype(np.float32)
+    shape = hk.Shape(L, H, d, t0, batch, dtype)
+    plan = hk.heatkv_build_schedule(shape, beta0, B * 2 * d * esz, s, variant)
+    ref = harness.oracle_schedule(beta0, L, H, t0, s, B, variant=variant)
+    binary = bool(variant & 1)
+    assert any(len(ref["sch"]["E"][k]) > 0 for k in range(1, K))
+    for k in range(K):
+        assert np.array_equal(plan.sets(k, hk.binding.SET_A), harness.bitmap(ref["sch"]["A"][k + 1], K, L, H, s, binary))
+    if binary:  # every head holds either everything or the sinks only
+        for k in range(K):
+            for l in range(L):
+                assert set(plan.runs(k, l)[1].tolist()) <= {c[k - 1] if k else 0, c[min(s, k) - 1] if min(s, k) else 0}
+    qkv = [hi.make_qkv(50 + variant, l, cfg, w=w) for l in range(L)]
+    outs = _generation_all_layers(plan, [_dev(*x) for x in qkv], t0, sm, fused_layers=(1,))
+    worst = 0.0
+    for l in range(L):
+        for kk in range(K):
+            for h in range(H):
+                kept = [i + 1 for i in range(kk) if ref["present"][kk, l, h, i]]
+                assert kept == orc.retained_scales(ref["sch"]["A"][kk + 1], kk + 1, l + 1, h + 1, s, binary=binary)
+                assert np.array_equal(plan.retained(kk, l, h), orc.retained_token_indices(ref["t"], kk + 1, kept))
+        worst = max(worst, _check_all(outs[l], *qkv[l], t0, ref["present"], l, sm, TOL[dtype]))
+    print(f"variant {variant} {dtype}: worst |err| {worst:.2e}")
 
 
 def test_bf16_small_ragged_scales():
@@ -301,20 +368,20 @@ def test_bf16_rising_logits_exercise_lazy_rescale():
 
 def test_mfma_probe_runs_and_is_deterministic():
     # measurement aid: same operands, same sums; zero operands give zeros
-    n = hk.heatkv_probe_mfma_operand_bytes() // 2
+    n = hp.heatkv_probe_mfma_operand_bytes() // 2
     g = torch.Generator(device="cuda").manual_seed(3)
     ops = torch.randn(n, device="cuda", generator=g).to(torch.bfloat16)
     out1 = torch.empty(4 * 256, device="cuda")
     out2 = torch.empty(4 * 256, device="cuda")
-    hk.heatkv_probe_mfma(ops, out1, 4, 3)
-    hk.heatkv_probe_mfma(ops, out2, 4, 3)
+    hp.heatkv_probe_mfma(ops, out1, 4, 3)
+    hp.heatkv_probe_mfma(ops, out2, 4, 3)
     torch.cuda.synchronize()
     assert torch.equal(out1, out2) and torch.isfinite(out1).all() and out1.abs().max() > 0
-    hk.heatkv_probe_mfma(torch.zeros_like(ops), out1, 4, 3)
+    hp.heatkv_probe_mfma(torch.zeros_like(ops), out1, 4, 3)
     torch.cuda.synchronize()
     assert (out1 == 0).all()
     with pytest.raises(hk.HeatKVError):
-        hk.heatkv_probe_mfma(ops, out1, 0, 3)
+        hp.heatkv_probe_mfma(ops, out1, 0, 3)
 
 
 def test_rank_dispersion_over_gpu_calibration_runs():
@@ -528,38 +595,38 @@ def test_calibrate_instances_write_the_same_bits():
 
 
 def test_tile_step_probe_runs_and_is_deterministic():
-    n = hk.heatkv_probe_tile_step_bytes() // 2
+    n = hp.heatkv_probe_tile_step_bytes() // 2
     g = torch.Generator(device="cuda").manual_seed(4)
     tiles = torch.randn(n, device="cuda", generator=g).to(torch.bfloat16)
     out1 = torch.empty(6 * 256, device="cuda")
     out2 = torch.empty(6 * 256, device="cuda")
-    hk.heatkv_probe_tile_step(tiles, out1, 6, 4)
-    hk.heatkv_probe_tile_step(tiles, out2, 6, 4)
+    hp.heatkv_probe_tile_step(tiles, out1, 6, 4)
+    hp.heatkv_probe_tile_step(tiles, out2, 6, 4)
     torch.cuda.synchronize()
     assert torch.equal(out1, out2)
     with pytest.raises(hk.HeatKVError):
-        hk.heatkv_probe_tile_step(tiles, out1, 6, 3)  # odd step count
+        hp.heatkv_probe_tile_step(tiles, out1, 6, 3)  # odd step count
     with pytest.raises(ValueError):
-        hk.heatkv_probe_tile_step(tiles[:100], out1, 6, 4)
+        hp.heatkv_probe_tile_step(tiles[:100], out1, 6, 4)
 
 
 def test_tile_stream_probe_copies_what_it_claims():
     # The read-bandwidth probe is the attention kernel's tile copy without arithmetic; its checksum words prove
     # that every step of every workgroup went through LDS in source order.
     wgs, steps = 6, 5
-    nbytes = hk.heatkv_probe_tile_stream_bytes(wgs, steps)
+    nbytes = hp.heatkv_probe_tile_stream_bytes(wgs, steps)
     assert nbytes == wgs * steps * 32768
     g = torch.Generator(device="cuda").manual_seed(7)
     src = torch.randint(-2**31, 2**31 - 1, (wgs, steps, 8192), dtype=torch.int32, device="cuda", generator=g)
     out = torch.zeros(wgs, 256, dtype=torch.int32, device="cuda")
-    hk.heatkv_probe_tile_stream(src, out, wgs, steps)
+    hp.heatkv_probe_tile_stream(src, out, wgs, steps)
     torch.cuda.synchronize()
     want = src[:, 0, :256].clone()
     for t in range(1, steps):
         want ^= src[:, t, :256]
     assert torch.equal(out, want)
     with pytest.raises(hk.HeatKVError):
-        hk.heatkv_probe_tile_stream(src, out, wgs, steps + 1)  # source too small
+        hp.heatkv_probe_tile_stream(src, out, wgs, steps + 1)  # source too small
     with pytest.raises(hk.HeatKVError):
-        hk.heatkv_probe_tile_stream(src, out, 0, steps)
+        hp.heatkv_probe_tile_stream(src, out, 0, steps)
 
