@@ -93,6 +93,18 @@ size_t heatkv_calibrate_workspace_bytes(const heatkv_shape* shape, int k1);
 int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
                      float sm_scale, float* mass, void* ws, size_t ws_bytes, void* stream);
 
+/* heatkv_calibrate for callers that cannot allocate device memory or pass a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same arithmetic and the
+ * same bits in `mass` as heatkv_calibrate; the per-tile partial sums go to a 1 MiB array that the library holds
+ * in static device memory (one copy per GPU, for the life of the process) instead of `ws`.  The call allocates
+ * nothing.  HEATKV_EINVAL, before any GPU work, if heatkv_calibrate_workspace_bytes(shape, k1) exceeds 1 MiB
+ * (1048576 bytes; e.g. batch 32 x 16 heads x 13 scales fits up to t[k1] = 4992).  All calls on one GPU share
+ * the array: two such calls that overlap in time on the same GPU (different streams, different threads) race;
+ * issue them on one stream or order them otherwise.  Nothing in the array has to start at zero (every partial
+ * that is read was written by the same call first). */
+int heatkv_calibrate_static(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
+                            float sm_scale, float* mass, void* stream);
+
 /* Dataset average of Eq. 2 (Sec. 3.1: beta is the mean of beta^d over the
  * calibration set; every batch row is one data point):
  *     beta[layer][h][k1][k2] += weight * sum_b mass[b][h][k2]

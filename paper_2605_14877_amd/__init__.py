@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     heatkv_calibrate,
     heatkv_calibrate_accumulate,
     heatkv_calibrate_scales_accumulate,
+    heatkv_calibrate_static,
     heatkv_head_scores,
     heatkv_load_schedule,
     heatkv_rank_dispersion,

@@ -55,6 +55,8 @@ def lib():
     L.heatkv_calibrate_workspace_bytes.argtypes = [sp, C.c_int]
     L.heatkv_calibrate.restype = C.c_int
     L.heatkv_calibrate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+    L.heatkv_calibrate_static.restype = C.c_int
+    L.heatkv_calibrate_static.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, vp, vp]
     L.heatkv_calibrate_accumulate.restype = C.c_int
     L.heatkv_calibrate_accumulate.argtypes = [sp, C.c_int, C.c_int, vp, vp, C.c_float, C.c_float, vp, vp, vp,
                                               C.c_size_t, vp]
@@ -292,6 +294,13 @@ def heatkv_calibrate(shape, layer, k1, q, k_all, sm_scale, mass, ws, stream=None
 
 
 calibrate = heatkv_calibrate
+
+
+def heatkv_calibrate_static(shape, layer, k1, q, k_all, sm_scale, mass, stream=None):
+    """heatkv_calibrate with the library's static workspace: no allocation, no workspace argument."""
+    _check_calibrate_operands(shape, k1, q, k_all, mass, None)
+    _check(lib().heatkv_calibrate_static(shape.ref, layer, k1, _ptr(q), _ptr(k_all), float(sm_scale), _ptr(mass),
+                                         _stream() if stream is None else stream))
 
 
 def heatkv_accumulate_beta(shape, layer, k1, mass, weight, beta, stream=None):

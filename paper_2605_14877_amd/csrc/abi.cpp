@@ -406,6 +406,26 @@ int heatkv_calibrate(const heatkv_shape* shape, int layer, int k1, const void* q
   return calibrate_impl(shape, layer, 1, &k, &q, &k_all, sm_scale, &mass, 0.f, nullptr, ws, ws_bytes, stream);
 }
 
+int heatkv_calibrate_static(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
+                            float sm_scale, float* mass, void* stream) {
+  if (!mass) return fail(HEATKV_EINVAL, "null tensor pointer");
+  // size first: a shape that does not fit is refused before any HIP call
+  const size_t need = heatkv_calibrate_workspace_bytes(shape, k1);
+  if (need > heatkv::kCalibrateStaticBytes)
+    return fail(HEATKV_EINVAL, "calibrate_static: batch*H*ceil(t[k1]/128)*K*4 = " + std::to_string(need) +
+                                   " bytes of partial sums exceed the static workspace of " +
+                                   std::to_string(heatkv::kCalibrateStaticBytes) + " bytes; use heatkv_calibrate");
+  int rc = heatkv::check_shape(shape);
+  if (rc) return rc;
+  if (k1 < 0 || k1 >= shape->K) return fail(HEATKV_EINVAL, "scale index out of range");
+  void* ws = nullptr;
+  hipError_t e = heatkv::calibrate_static_workspace(&ws);
+  if (e != hipSuccess) return hip_fail(e, "static workspace lookup");
+  const int32_t k = k1;
+  return calibrate_impl(shape, layer, 1, &k, &q, &k_all, sm_scale, &mass, 0.f, nullptr, ws,
+                        heatkv::kCalibrateStaticBytes, stream);
+}
+
 int heatkv_calibrate_accumulate(const heatkv_shape* shape, int layer, int k1, const void* q, const void* k_all,
                                 float sm_scale, float weight, float* beta, float* mass, void* ws, size_t ws_bytes,
                                 void* stream) {

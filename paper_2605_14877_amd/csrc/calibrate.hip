@@ -13,6 +13,7 @@
 // result is bit-reproducible (no floating-point atomics anywhere).
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "device_util.h"
@@ -521,6 +522,31 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(calibrate_finish_kernel, dim3((total + 255) / 256, a.n_scales), dim3(256), 0, stream, p, qpt);
   }
   return hipGetLastError();
+}
+
+// Workspace for callers that cannot allocate: the per-tile partial sums live in this file-scope device array
+// instead of a caller buffer.  Every GPU the library runs on holds its own copy at its own address until the
+// process ends; the array's name is only a host-side handle, the device address comes from
+// hipGetSymbolAddress, once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[kCalibrateStaticBytes];
+
+hipError_t calibrate_static_workspace(void** ptr) {
+  static std::mutex mu;
+  static void* per_device[64] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!per_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  return hipSuccess;
 }
 
 hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,

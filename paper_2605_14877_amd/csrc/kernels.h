@@ -64,6 +64,10 @@ size_t calibrate_workspace_bytes(int dtype, int d, int H, int batch, int K, int 
 size_t calibrate_scales_workspace_bytes(int dtype, int d, int H, int batch, int K, const int32_t* t, int n_scales,
                                         const int32_t* k1);
 hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream);
+// The library's own calibrate workspace on the current device: a static device array of kCalibrateStaticBytes
+// (looked up once per device, no allocation).  Calls that use it on one GPU share it.
+constexpr size_t kCalibrateStaticBytes = size_t(1) << 20;
+hipError_t calibrate_static_workspace(void** ptr);
 // beta[(layer*H + h)*K*K + k1*K + k2] += weight * sum_b mass[(b*H + h)*K + k2]
 hipError_t launch_accumulate_beta(int H, int batch, int K, int layer, int k1, const float* mass, float weight,
                                   float* beta, hipStream_t stream);

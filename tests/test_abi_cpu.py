@@ -393,3 +393,15 @@ def test_library_binary_variants_on_the_hand_worked_instance(variant):
     # head (1,1) at paper scale 4 keeps scales 1-3 under Binary-HeatKV (evicted after its layer), sinks only if naive
     want = list(range(0, 7)) if variant == binding.VARIANT_BINARY else [0]
     assert plan.retained(3, 0, 0).tolist() == want
+
+
+def test_calibrate_static_rejects_what_does_not_fit_before_any_gpu_call():
+    # 16 x 64 heads x ceil(4096/128) tiles x 13 scales x 4 bytes = 1.7 MB of partial sums: over the 1 MiB of the
+    # library's static workspace.  The size is checked before any HIP call or pointer use, so dummy addresses do.
+    t0 = hi.tokens_per_scale(hi.SIDES_1024)
+    shape = hk.Shape(1, 64, 128, t0, 16, "bf16")
+    assert binding.calibrate_workspace_bytes(shape, 12) > (1 << 20)
+    rc = binding.lib().heatkv_calibrate_static(shape.ref, 0, 12, 256, 256, 0.1, 256, None)
+    assert rc == -1 and b"exceed the static workspace" in binding.lib().heatkv_last_error()
+    fits = hk.Shape(1, 16, 128, t0, 32, "bf16")
+    assert binding.calibrate_workspace_bytes(fits, 12) <= (1 << 20)
