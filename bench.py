@@ -61,16 +61,17 @@ def main():
     ap.add_argument("--workload", default="layer2b",
                     choices=["layer2b", "serving_layer", "layer8b", "stack2b", "stack8b", "serving"],
                     help="layer2b (default): one 2B-like layer, the whole path.  *_layer / layer8b: one layer of the "
-                         "named stack.  stack2b / stack8b / serving: every layer of the stack, generation-order "
-                         "attend + append only (schedule from a fabricated beta table, no calibration pass)")
+                         "named stack.  stack2b / stack8b / serving: every layer of the stack, attend + append only "
+                         "(schedule from a fabricated beta table, no calibration pass), --steps passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend-only", action="store_true", help="profiling aid: skip calibrate/schedule in the step")
     ap.add_argument("--calibrate-per-scale", action="store_true",
                     help="calibrate with one call per scale instead of one launch for all scales")
     ap.add_argument("--separate-append", action="store_true",
                     help="call heatkv_attend_scale and heatkv_append_scale separately instead of the fused entry point")
-    ap.add_argument("--graph", action="store_true",
-                    help="stack workloads only: capture one generation pass in a HIP graph and time its replays")
+    ap.add_argument("--stack-passes", default="both", choices=["both", "generation", "batched"],
+                    help="stack workloads only: generation-order passes (attention + update fused, per-image time), "
+                         "scale-batched passes (per-scale kernel durations of attention and update), or both")
     ap.add_argument("--no-stack-20x", action="store_true",
                     help="default workload only: skip the two 20x stacks that supply the per-image attention time")
     ap.add_argument("--no-mfma-probe", action="store_true",
@@ -162,9 +163,28 @@ def main():
     att_bytes = [2.0 * d * esz * (n_keys[i] + nb * H * t0[i]) for i in range(K)]
     cal_flops = [2.0 * d * t0[i] * c[i] * nb * H for i in range(K)]
 
+    # Timed region: ONE event pair per step around the block of K attention launches (an event pair per launch
+    # would put two event records and their host time between launches of 7 us).  The per-scale breakdown comes
+    # from a second set of passes after the timed region, with a pair per launch.
+    blk_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    cal_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
           for _ in range(args.steps)]
-    cal_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+
+    def attend_block(pairs=None):
+        for kk in range(K):
+            if pairs is not None:
+                pairs[kk][0].record()
+            if args.separate_append:
+                hk.heatkv_attend_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk], att_ws[kk])
+                if pairs is not None:
+                    pairs[kk][1].record()
+                hk.heatkv_append_scale(plan, 0, kk, k_s[kk], v_s[kk], ka, va)
+            else:  # attention and cache update of the scale in one launch (an event pair then covers both)
+                hk.heatkv_attend_append_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk],
+                                              att_ws[kk])
+                if pairs is not None:
+                    pairs[kk][1].record()
 
     def step(i_timed=None):
         nonlocal plan
@@ -175,19 +195,11 @@ def main():
             if i_timed is not None:
                 cal_ev[i_timed][1].record()
             assert plan.arena_bytes <= arena_bytes
-        for kk in range(K):
-            if i_timed is not None:
-                ev[i_timed][kk][0].record()
-            if args.separate_append:
-                hk.heatkv_attend_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk], att_ws[kk])
-                if i_timed is not None:
-                    ev[i_timed][kk][1].record()
-                hk.heatkv_append_scale(plan, 0, kk, k_s[kk], v_s[kk], ka, va)
-            else:  # attention and cache update of the scale in one launch (the event pair then covers both)
-                hk.heatkv_attend_append_scale(plan, 0, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk],
-                                              att_ws[kk])
-                if i_timed is not None:
-                    ev[i_timed][kk][1].record()
+        if i_timed is not None:
+            blk_ev[i_timed][0].record()
+        attend_block()
+        if i_timed is not None:
+            blk_ev[i_timed][1].record()
 
     for _ in range(args.warmup):
         step()
@@ -198,10 +210,13 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
+    total_att_ms = float(np.mean([a.elapsed_time(b) for a, b in blk_ev]))
 
+    for i in range(args.steps):  # per-scale breakdown, outside the timed region
+        attend_block(ev[i])
+    torch.cuda.synchronize()
     att_ms = np.array([[ev[i][kk][0].elapsed_time(ev[i][kk][1]) for kk in range(K)] for i in range(args.steps)])
     att_ms_k = att_ms.mean(0)
-    total_att_ms = float(att_ms_k.sum())
     step_flops = sum(att_flops) + (0.0 if args.attend_only else sum(cal_flops))
     value = step_flops / (ms_per_step * 1e-3) / 1e12
     att_tflops = sum(att_flops) / (total_att_ms * 1e-3) / 1e12
@@ -238,8 +253,9 @@ def main():
                                f"{K} scales ({c[-1]} tokens), {cfg['factor']}x budget, sinks {s}",
                    "attend_only": bool(args.attend_only), "fused_append": not args.separate_append,
                    "calibrate": "per scale" if args.calibrate_per_scale else "all scales in one launch"},
-        "value_is": "heatkv_attend_scale algorithmic TFLOP/s over the 13 launches of a step (HIP events around each "
-                    "launch, fused cache update included unless --separate-append)",
+        "value_is": "heatkv_attend_scale algorithmic TFLOP/s over the 13 launches of a step (one HIP event pair "
+                    "around the block of launches in every timed step; fused cache update included unless "
+                    "--separate-append); per_scale: event pair per launch, passes after the timed region",
         "whole_step_tflops": round(value, 3),
         "attend_scale_tflops": round(att_tflops, 2),
         "attend_scale_ms_per_step": round(total_att_ms, 4),
@@ -276,8 +292,14 @@ def main():
             att_flops[K - 1] / (att_ms_k[K - 1] * 1e-3) / 1e12 / probe["random_operands"], 4)
         result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
     if not args.no_stack_20x and not args.attend_only:
-        del ka, va
-        result["per_image_attention_ms_at_20x"] = per_image_ms_at_20x(args, dev)
+        del ka, va, q_s, k_s, v_s, kall_s, out_s, dq, dk, dv
+        torch.cuda.empty_cache()
+        stacks = {name: stack_measure(name, dev, passes=2, warmup=1) for name in ("stack8b", "serving")}
+        result["per_image_attention_ms_at_20x"] = {name: r["ms_per_image"] for name, r in stacks.items()}
+        result["stacks_20x"] = stacks
+        result["roofline_hbm"] = hbm_leg(stacks["serving"])
+        result["roofline_mfma_large_scales"] = mfma_leg(stacks["serving"])
+        result["append_kernel"] = append_leg(stacks["serving"])
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -373,44 +395,52 @@ def hbm_read_probe(dev):
 
 
 def run_stack(args, dev):
-    """Generation-order attend + append over every layer of a stack config (no calibration pass)."""
-    result = stack_result(args, dev)
+    """--workload stack2b / stack8b / serving: the stack measurement alone, as one JSON line (profiling aid)."""
+    r = stack_measure(args.workload, dev, passes=args.steps, warmup=args.warmup,
+                      generation=args.stack_passes in ("both", "generation"),
+                      batched=args.stack_passes in ("both", "batched"))
+    value = r.get("attend_tflops_generation_order")
+    result = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r.get("ms_per_pass"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": r["workload"] + "; schedule from a fabricated beta table; attend + append only",
+                   "stack_passes": args.stack_passes},
+        "value_is": "heatkv_attend_scale algorithmic TFLOP/s over a generation-order pass of the whole stack "
+                    "(attention + cache update in one launch per layer and scale, host clock)",
+        "stack": r,
+    }
+    if r.get("per_scale"):
+        result["roofline"] = mfma_leg(r)
+        result["roofline_hbm"] = hbm_leg(r)
+        result["append_kernel"] = append_leg(r)
     if not args.no_mfma_probe:
-        probe = mfma_probe(dev)
-        result["roofline"]["mfma_probe"] = probe
-        result["roofline"]["frac_of_probe_random"] = round(result["value"] / probe["random_operands"], 4)
-        result["roofline"]["hbm_read_probe"] = hbm_read_probe(dev)
+        result["mfma_probe"] = mfma_probe(dev)
+        result["hbm_read_probe"] = hbm_read_probe(dev)
     print(json.dumps(result))
 
 
-def per_image_ms_at_20x(args, dev):
-    """Per-image attention time over a whole stack at the 20x budget (the third figure of the headline metric):
-    the 8B-like stack (batch 2 = one image with its CFG row) and the serving stack (batch 32 = 16 images), one
-    warm-up pass and two timed passes each."""
-    import copy
-
-    out = {}
-    for name in ("stack8b", "serving"):
-        a = copy.copy(args)
-        a.workload, a.steps, a.warmup, a.graph, a.separate_append = name, 2, 1, False, False
-        r = stack_result(a, dev)
-        out[name] = {"ms_per_image": r["per_image_attention_ms"], "attend_tflops": r["value"],
-                     "images_per_pass": max(r["batch"] // 2, 1)}
-    return out
-
-
-def stack_result(args, dev):
+def stack_measure(name, dev, passes, warmup, generation=True, batched=True):
+    """One 20x stack (stack8b: one image with its CFG row; serving: 16 images), every layer with activations of
+    its own (nothing a launch reads was touched by the launches just before it, so K/V, Q and the current scale
+    come from HBM, not from L2 or the memory-side cache).  Two kinds of passes:
+      * generation order (for every scale, for every layer: attention + cache update in one launch), timed as a
+        whole on the host clock between device synchronisations: per-image attention time;
+      * scale-batched (for every scale: the L attention launches back to back between one event pair, then the
+        L cache-update launches between another): average duration per launch of either kernel at every scale,
+        hence TFLOP/s, KV GB/s and the copy bandwidth of the update.  Legal because an update only retires its own
+        layer's region of the scale, which only that layer's attention reads, and the updates keep their order."""
     import torch
 
     import heatkv_inputs as hi
     import paper_2605_14877_amd as hk
-    from paper_2605_14877_amd import probe as hp
 
-    cfg = hi.CONFIGS[args.workload]
+    cfg = hi.CONFIGS[name]
     t0 = hi.tokens_per_scale(cfg["sides"])
     c = hi.cumulative_tokens(t0)
     L, K, H, d, s, nb = cfg["L"], len(t0), cfg["H"], cfg["d"], cfg["sinks"], cfg["batch"]
     esz = hi.elem_bytes(cfg["dtype"])
+    row = d * esz
     sm = 1.0 / np.sqrt(d)
     B = hi.budget_tokens(cfg)
     w = hi.head_weights(0, L, H, K)
@@ -418,84 +448,136 @@ def stack_result(args, dev):
     shape = hk.Shape(L, H, d, t0, nb, cfg["dtype"])
     plan = hk.heatkv_build_schedule(shape, beta, B * 2 * d * esz, s)
     plan.upload()
-    # one set of activations, reused by every layer (same shapes and value distribution; the plan differs per layer)
-    q, k, v = hi.make_qkv_device(0, 0, cfg, w, dev)
     sl = [slice(c[i] - t0[i], c[i]) for i in range(K)]
-    q_s = [q[:, :, sl[i]].contiguous() for i in range(K)]
-    k_s = [k[:, :, sl[i]].contiguous() for i in range(K)]
-    v_s = [v[:, :, sl[i]].contiguous() for i in range(K)]
-    out_s = [torch.empty_like(x) for x in q_s]
-    del q, k, v
+    acts = []  # acts[l][kk] = (q, k, v, out)
+    for l in range(L):
+        q, k, v = hi.make_qkv_device(l, l, cfg, w, dev)
+        acts.append([(q[:, :, sl[i]].contiguous(), k[:, :, sl[i]].contiguous(), v[:, :, sl[i]].contiguous(),
+                      torch.empty_like(q[:, :, sl[i]])) for i in range(K)])
+        del q, k, v
     ka = torch.zeros(max(plan.arena_bytes, 16), dtype=torch.uint8, device=dev)
     va = torch.zeros_like(ka)
-    flops = np.zeros(K)
-    byts = np.zeros(K)
+    flops, byts, app_rows = np.zeros(K), np.zeros(K), np.zeros(K)
     for kk in range(K):
         for l in range(L):
             n = nb * int((plan.runs(kk, l)[1].astype(np.int64) + t0[kk]).sum())
             flops[kk] += 4.0 * t0[kk] * d * n
-            byts[kk] += 2.0 * d * esz * (n + nb * H * t0[kk])
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
-          for _ in range(args.steps)]
+            byts[kk] += 2.0 * row * (n + nb * H * t0[kk])
+            if kk + 1 < K:  # rows the update writes: the whole region the next scale reads
+                app_rows[kk] += nb * int(plan.runs(kk + 1, l)[1].astype(np.int64).sum())
 
-    def step(i_timed=None):
+    def generation_pass():
         for kk in range(K):
             for l in range(L):
-                if i_timed is not None and l == 0:
-                    ev[i_timed][kk][0].record()
-                if args.separate_append:
-                    hk.heatkv_attend_scale(plan, l, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk])
-                    hk.heatkv_append_scale(plan, l, kk, k_s[kk], v_s[kk], ka, va)
-                else:
-                    hk.heatkv_attend_append_scale(plan, l, kk, q_s[kk], k_s[kk], v_s[kk], ka, va, sm, out_s[kk])
-            if i_timed is not None:
-                ev[i_timed][kk][1].record()
+                q, k, v, o = acts[l][kk]
+                hk.heatkv_attend_append_scale(plan, l, kk, q, k, v, ka, va, sm, o)
 
-    graph = None
-    if args.graph:
-        # The entry points only enqueue kernels once the plan is uploaded, so a whole pass can be captured.
-        step()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        graph.replay() if graph else step()
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        graph.replay() if graph else step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
-    if graph:  # no per-scale events inside a graph: one eager pass supplies the per-scale split
-        step(0)
-        torch.cuda.synchronize()
-        scale_ms = np.array([a.elapsed_time(b) for a, b in ev[0]])
-    else:
-        scale_ms = np.array([[a.elapsed_time(b) for a, b in row] for row in ev]).mean(0)  # attend + append, L layers
-    value = flops.sum() / (ms_per_step * 1e-3) / 1e12
-    result = {
-        "metric": "attend_scale algorithmic TFLOP/s over generation-order attend + append of the whole stack",
-        "value": round(float(value), 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {L} layers x {H} heads x d{d} {cfg['dtype']}, batch {nb}, {K} scales, "
-                               f"{cfg['factor']}x budget, sinks {s}; schedule from a fabricated beta table; "
-                               f"attend + append only", "hip_graph": bool(args.graph)},
-        "per_image_attention_ms": round(ms_per_step / max(nb // 2, 1), 4),
-        "batch": nb,
-        "kv_cache_budget_mb": round(nb * B * 2 * d * esz / 1e6, 1),
-        "arena_mb": round(2 * plan.arena_bytes / 1e6, 1),
-        "arena_tokens_over_budget": round(plan.arena_tokens / B, 4),
-        "per_scale": [{"k": kk, "t": t0[kk], "ms": round(float(scale_ms[kk]), 4),
-                       "tflops": round(flops[kk] / (scale_ms[kk] * 1e-3) / 1e12, 2),
-                       "gbs": round(byts[kk] / (scale_ms[kk] * 1e-3) / 1e9, 1)} for kk in range(K)],
-        "roofline": {"kernel": "attend_bf16_d128_kernel (+ append_kernel inside the timed pairs)", "bound": "mfma",
-                     "achieved": round(float(value), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(float(value) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    def batched_pass(ev_att, ev_app):
+        for kk in range(K):
+            ev_att[kk][0].record()
+            for l in range(L):
+                q, k, v, o = acts[l][kk]
+                hk.heatkv_attend_scale(plan, l, kk, q, k, v, ka, va, sm, o)
+            ev_att[kk][1].record()
+            ev_app[kk][0].record()
+            for l in range(L):
+                q, k, v, o = acts[l][kk]
+                hk.heatkv_append_scale(plan, l, kk, k, v, ka, va)
+            ev_app[kk][1].record()
+
+    out = {
+        "workload": f"{name}: {L} layers x {H} heads x d{d} {cfg['dtype']}, batch {nb}, {K} scales, "
+                    f"{cfg['factor']}x budget, sinks {s}; per-layer activations ({L} distinct sets)",
+        "passes": passes, "images_per_pass": max(nb // 2, 1),
+        "arena_tokens_over_budget": round(plan.arena_tokens / B, 4), "launches_per_scale": L,
     }
-    return result
+    if generation:
+        for _ in range(warmup):
+            generation_pass()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(passes):
+            generation_pass()
+        torch.cuda.synchronize()
+        ms_per_pass = (time.perf_counter() - t_start) * 1e3 / passes
+        out.update({"ms_per_pass": round(ms_per_pass, 3), "ms_per_image": round(ms_per_pass / max(nb // 2, 1), 3),
+                    "attend_tflops_generation_order": round(float(flops.sum()) / ms_per_pass / 1e9, 1)})
+    if not batched:
+        return out
+
+    mk = lambda: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    evs = [(mk(), mk()) for _ in range(passes)]
+    if not generation:
+        for _ in range(warmup):
+            batched_pass(mk(), mk())
+    for ea, ep in evs:
+        batched_pass(ea, ep)
+    torch.cuda.synchronize()
+    att_us = np.array([[a.elapsed_time(b) for a, b in ea] for ea, _ in evs]).mean(0) * 1e3 / L
+    app_us = np.array([[a.elapsed_time(b) for a, b in ep] for _, ep in evs]).mean(0) * 1e3 / L
+    rows = []
+    for kk in range(K):
+        fl, by = flops[kk] / L, byts[kk] / L  # per launch
+        ab = 2.0 * 2.0 * row * app_rows[kk] / L  # K and V rows, each read once and written once
+        rows.append({
+            "k": kk, "t": t0[kk], "attend_us": round(float(att_us[kk]), 2),
+            "tflops": round(fl / att_us[kk] / 1e6, 1), "pct_mfma_peak": round(100 * fl / att_us[kk] / 1e6 / PEAK_BF16_TFLOPS, 2),
+            "kv_mb": round(by / 1e6, 2), "kv_gbs": round(by / att_us[kk] / 1e3, 1),
+            "pct_hbm_peak": round(100 * by / att_us[kk] / 1e3 / PEAK_HBM_GBS, 2),
+            "flop_per_byte": round(fl / by, 1),
+            "append_us": round(float(app_us[kk]), 2), "append_mb": round(ab / 1e6, 2),
+            "append_gbs": round(ab / app_us[kk] / 1e3, 1) if kk + 1 < K else None,
+        })
+    out.update({"attend_ms_per_pass_kernel_only": round(float(att_us.sum()) * L / 1e3, 3),
+                "append_ms_per_pass_kernel_only": round(float(app_us.sum()) * L / 1e3, 3), "per_scale": rows})
+    return out
+
+
+def hbm_leg(stack):
+    """Second leg of the headline metric: KV GB/s of the attention launches bound by the K/V read: scales of at
+    most 256 tokens (arithmetic intensity 22-172 FLOP/B, under the chip's ridge of 312) whose launch moves at
+    least 16 MB; on the serving stack those are the scales of 36, 64, 144 and 256 tokens."""
+    rows = [r for r in stack["per_scale"] if r["kv_mb"] >= 16.0 and r["t"] <= 256]
+    if not rows:
+        return None
+    by = sum(r["kv_mb"] for r in rows) * 1e6
+    us = sum(r["attend_us"] for r in rows)
+    gbs = by / us / 1e3
+    return {"kernel": "attend_bf16_d128_kernel", "workload": stack["workload"], "bound": "hbm",
+            "launches": [r["t"] for r in rows], "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": measured_traffic("serving_small_scales"),
+            "algorithmic_bytes_per_launch": round(by / max(len(rows), 1)),
+            "avg_launch_us": round(us / max(len(rows), 1), 2),
+            "per_scale": [{k: r[k] for k in ("t", "attend_us", "kv_mb", "kv_gbs", "pct_hbm_peak", "tflops",
+                                             "flop_per_byte")} for r in rows]}
+
+
+def mfma_leg(stack):
+    """The matrix-core leg on a full chip: serving-stack launches of 1024 tokens and more."""
+    rows = [r for r in stack["per_scale"] if r["t"] >= 1024]
+    if not rows:
+        return None
+    fl = sum(r["tflops"] * r["attend_us"] for r in rows)
+    us = sum(r["attend_us"] for r in rows)
+    return {"kernel": "attend_bf16_d128_kernel", "workload": stack["workload"], "bound": "mfma",
+            "launches": [r["t"] for r in rows], "achieved": round(fl / us, 1), "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(fl / us / PEAK_BF16_TFLOPS, 4),
+            "per_scale": [{k: r[k] for k in ("t", "attend_us", "tflops", "pct_mfma_peak")} for r in rows]}
+
+
+def append_leg(stack):
+    """The cache-update kernel as a copy: bytes read + written per launch over its duration, serving stack,
+    launches that move at least 16 MB."""
+    rows = [r for r in stack["per_scale"] if r["append_gbs"] is not None and r["append_mb"] >= 16.0]
+    if not rows:
+        return None
+    by = sum(r["append_mb"] for r in rows) * 1e6
+    us = sum(r["append_us"] for r in rows)
+    return {"kernel": "append_kernel", "workload": stack["workload"], "bound": "hbm",
+            "achieved": round(by / us / 1e3, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(by / us / 1e3 / PEAK_HBM_GBS, 4), "traffic": None,
+            "bytes_per_launch": round(by / len(rows)), "avg_launch_us": round(us / len(rows), 2),
+            "per_scale": [{k: r[k] for k in ("t", "append_us", "append_mb", "append_gbs")} for r in rows]}
 
 
 def cpu_baseline(q, k, v, t0, plan, sm, d):
