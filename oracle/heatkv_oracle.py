@@ -24,7 +24,11 @@ that Eq. 5 and that total imply (every newly pruned head outside the first
 layer is pruned early, none of the first layer is), against a replay of the
 cache contents head by head, and brute-force minimum cardinality (Prop. 1);
 the rank dispersion of App. C against closed forms (identical runs, reversed
-orders) and against numpy's argsort/std on random tables.
+orders) and against numpy's argsort/std on random tables; the 8-bit cache
+format against the values the OCP FP8 specification fixes (smallest subnormal,
+smallest normal, one, 448, NaN), the round trip of all 256 codes, hand-worked
+ties, saturation, and torch's float8_e4m3fn cast on random values inside the
+finite range.
 Minimum cardinality of E_k is not a property of the scale-dependent variant
 (the paper proves it for the binary case only): a hand-worked instance,
 tests/golden/alg1_scale_dependent_not_minimal.txt, has the greedy order of
@@ -106,6 +110,63 @@ def attend_scale(q_seq, k_seq, v_seq, t, k, retained_scales, sm_scale):
     cur = np.arange(c[k - 1], c[k])
     keys_idx = np.concatenate([retained_token_indices(t, k, retained_scales), cur])
     return attend(q_seq[cur], k_seq[keys_idx], v_seq[keys_idx], sm_scale)
+
+
+# --------------------------------------------------------------------------
+# 8-bit storage of the retained K/V (an extension of this build: the paper leaves quantisation of the cache to
+# future work, Sec. 5, and fixes no format; the format taken here is stated in the design doc)
+#
+# Stored rows are OCP FP8 E4M3 codes: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits; exponent field 0
+# holds subnormals m * 2^-9; exponent 15 with mantissa 7 is NaN; there are no infinities; the largest finite
+# magnitude is 448.  A value is stored as the nearest representable one, ties to the code with an even mantissa,
+# magnitudes above 448 as 448 (saturating), NaN as NaN.  No scale factors.  Only what the cache holds is
+# rounded: the current scale's K/V are attended as the caller passes them.
+# --------------------------------------------------------------------------
+
+
+def fp8_e4m3_decode(codes):
+    """Values of E4M3 codes (uint8 array) as fp64, straight from the bit fields."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    sign = np.where(codes & 0x80, -1.0, 1.0)
+    e = ((codes >> 3) & 0xF).astype(np.int64)
+    m = (codes & 0x7).astype(np.float64)
+    normal = (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64))
+    subnormal = (m / 8.0) * 2.0 ** -6
+    out = sign * np.where(e == 0, subnormal, normal)
+    return np.where((e == 15) & ((codes & 0x7) == 7), np.nan, out)
+
+
+def fp8_e4m3_encode(x):
+    """Nearest E4M3 code of every value of x (any shape): the definition written out as a search over the 127
+    non-negative finite values, ties to the even code, saturating at 448; the sign is carried over."""
+    x = np.asarray(x, dtype=np.float64)
+    grid = fp8_e4m3_decode(np.arange(127, dtype=np.uint8))  # codes 0x00..0x7E, ascending
+    mag = np.minimum(np.abs(x), 448.0)
+    hi = np.clip(np.searchsorted(grid, mag, side="left"), 1, 126)  # grid[hi-1] <= mag <= grid[hi]
+    lo = hi - 1
+    d_lo, d_hi = mag - grid[lo], grid[hi] - mag
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))  # a code is even iff its mantissa's last bit is 0
+    code = np.where(take_hi, hi, lo).astype(np.uint8)
+    code = np.where(np.signbit(x), code | 0x80, code).astype(np.uint8)
+    return np.where(np.isnan(x), np.uint8(0x7F), code).astype(np.uint8)
+
+
+def fp8_e4m3_round(x):
+    """What a value reads back as after being stored in the 8-bit cache."""
+    return fp8_e4m3_decode(fp8_e4m3_encode(x))
+
+
+def attend_scale_fp8_cache(q_seq, k_seq, v_seq, t, k, retained_scales, sm_scale):
+    """attend_scale with the retained prior-scale rows of K and V read back from 8-bit storage; the rows of the
+    current scale keep their full precision."""
+    c = cumulative(t)
+    cur = np.arange(c[k - 1], c[k])
+    prior = retained_token_indices(t, k, retained_scales)
+    k_seq = np.asarray(k_seq, dtype=np.float64)
+    v_seq = np.asarray(v_seq, dtype=np.float64)
+    keys = np.concatenate([fp8_e4m3_round(k_seq[prior]), k_seq[cur]])
+    values = np.concatenate([fp8_e4m3_round(v_seq[prior]), v_seq[cur]])
+    return attend(np.asarray(q_seq, dtype=np.float64)[cur], keys, values, sm_scale)
 
 
 # --------------------------------------------------------------------------
