@@ -304,6 +304,15 @@ int attend_impl(heatkv_plan* plan, int layer, int k, const void* q, const void* 
   const size_t off = plan->idx(k, layer, 0);
   a.work = plan->dev.work + off;
   a.max_len = max_len;
+  {  // runs of equal length (no head of the layer has lost a scale yet): addresses follow from the head index
+    const int32_t* len = &plan->run_len[off];
+    bool uniform = true;
+    for (int h = 1; h < plan->H; ++h) uniform = uniform && len[h] == len[0];
+    if (uniform) {
+      a.uniform_len = len[0];
+      a.uniform_row0 = plan->run_row[off];
+    }
+  }
   a.q = q;
   a.k_cur = k_cur;
   a.v_cur = v_cur;

@@ -23,6 +23,10 @@ struct AttendParams {
   int H, batch, t_k;
   long long arena_tokens;
   const HeadWork* work;
+  // uniform_len >= 0: every head of the layer holds a run of that many rows, head h's run starts at row
+  // uniform_row0 + h * uniform_len, and (batch row, head) pairs are taken in index order: a workgroup then knows
+  // all its addresses from its id and the kernel arguments, and its first fetches do not wait for a table read.
+  int uniform_len, uniform_row0;
   const void *q, *k_cur, *v_cur, *k_arena, *v_arena;
   void* out;
   float sm_scale;
@@ -103,13 +107,21 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   if (pair >= p.H * p.batch) return;
   const int qt = slot % p.n_qtiles;
   const int b = pair % p.batch;
-  const HeadWork hw = p.work[pair / p.batch];  // one 16-byte record: head, first row and length of its run
-  const int h = hw.head;
+  int h, n_prior, run_row;
+  if (p.uniform_len >= 0) {
+    h = pair / p.batch;
+    n_prior = p.uniform_len;
+    run_row = p.uniform_row0 + h * p.uniform_len;
+  } else {
+    const HeadWork hw = p.work[pair / p.batch];  // one 16-byte record: head, first row and length of its run
+    h = hw.head;
+    n_prior = hw.run_len;
+    run_row = hw.run_row;
+  }
 
   const int t_k = p.t_k;
-  const int n_prior = hw.run_len;
   const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D128;
-  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + hw.run_row) * D128;
+  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + run_row) * D128;
   const char* k_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_arena) + run_off);
   const char* v_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_arena) + run_off);
   const char* k_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_cur) + cur_off);
@@ -282,40 +294,46 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   // V stage vb0.  s_in holds the scores of tile j, s_out receives those of tile j+1: the two register sets swap
   // roles from step to step instead of being copied.
   auto pipe_step = [&](int j, auto kb1, auto vb0, f32x16 (&s_in)[2], f32x16 (&s_out)[2]) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vmcnt<0>();
     __syncthreads();
     if (j + 2 < steps_all && has_tile(j + 2)) issue_k(j + 2, decltype(vb0)::value);  // K stage j & 1: read by step j-1
-    if (has_tile(j + 1)) issue_v(j + 1, decltype(kb1)::value);                       // V stage (j+1) & 1 likewise
+    // V stage (j+1) & 1 likewise; the single-stream prologue has already fetched V(1)
+    if ((KS == 2 || j > 0) && has_tile(j + 1)) issue_v(j + 1, decltype(kb1)::value);
     if (!active) return;
     if (has_tile(j + 1)) scores(s_out, kb1);
     accumulate(s_in, vb0);
     if (has_tile(j + 1)) settle(j + 1, s_out);
   };
 
-  // Prologue: K(0), K(1) and V(0) all go out at once (one memory round trip instead of two before the loop,
-  // which is what the short scales are made of); loads return in issue order, so waiting until at most the
-  // eight younger copies are outstanding means K(0) has landed.
+  // Prologue: all four tile stages are free, so K(0), V(0), K(1) and V(1) all go out at once: one memory round
+  // trip before the loop, and a walk of two tiles (every scale of up to 64 tokens) never waits for memory again.
+  // Loads return in issue order, so waiting until at most the twelve younger copies are outstanding means that
+  // K(0) has landed; tile 0 is a current-scale tile, whose address does not depend on the head's run.
   if (KS == 1) {
     issue_k(0, 0);
+    issue_v(0, 0);
     if (tiles_all > 1) {
       issue_k(1, 1);
-      issue_v(0, 0);
-      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      issue_v(1, 1);
+      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     } else {
-      issue_v(0, 0);
       asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     }
   } else {  // a stream may have no tile at all, or one: everything it has goes out, then a full wait
     if (has_tile(0)) issue_k(0, 0);
     if (steps_all > 1 && has_tile(1)) issue_k(1, 1);
     if (has_tile(0)) issue_v(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vmcnt<0>();
   }
   __syncthreads();
   if (active && has_tile(0)) {
     scores(s_cur, std::integral_constant<int, 0>{});
     settle(0, s_cur);
   }
+  // Every path reaches the loop through a full wait that the compiler sees (a wavefront that skipped the scores
+  // above never waited for its query rows): otherwise it waits for them inside every step, and with them for the
+  // tile copies that the step has just issued.  The first step starts with the same wait, so this one is free.
+  wait_vmcnt<0>();
   int it = 0;
   for (; it + 2 < steps_all; it += 2) {  // scores of even steps live in s_cur, of odd steps in s_nxt
     pipe_step(it, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, s_cur, s_nxt);
@@ -326,7 +344,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     ++it;
   }
   // Epilogue: the last tile has scores but no successor.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  wait_vmcnt<0>();
   __syncthreads();
   if (KS == 1 && !active) return;
   if (active && has_tile(it)) {
@@ -528,6 +546,8 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   p.t_k = a.t_k;
   p.arena_tokens = a.arena_tokens;
   p.work = a.work;
+  p.uniform_len = a.uniform_len;
+  p.uniform_row0 = a.uniform_row0;
   p.q = a.q;
   p.k_cur = a.k_cur;
   p.v_cur = a.v_cur;

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
     const int tiles_here = (p.t[k2] + CBN - 1) / CBN;
     const bool last_of_block = tile + 1 >= tiles_here;
     const int nk2 = last_of_block ? k2 + 1 : k2, ntile = last_of_block ? 0 : tile + 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vmcnt<0>();
     __syncthreads();
     if (nk2 <= k1) issue_tile(nk2, ntile, buf ^ 1);
     const char* kt = lds + buf * CTILE_BYTES;

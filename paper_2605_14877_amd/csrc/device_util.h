@@ -46,6 +46,21 @@ __device__ __forceinline__ float sum_halves(float v) {
   return a + b;
 }
 
+// s_waitcnt on the vector-memory counter alone (at most N loads outstanding), as an instruction the compiler
+// sees.  The tile copies of the bf16 kernels are issued as text the compiler does not look into, so it does not
+// count them, but the hardware counter does: a wait the compiler adds for one of ITS loads (the query rows, say)
+// then also waits for every tile copy issued before that point.  Where such a load may still be outstanding on
+// some path into a loop, the compiler repeats those waits in every iteration, i.e. in the middle of the math
+// right after the next tiles' copies went out.  A visible full wait at a point where the kernel waits anyway
+// tells it that nothing of its own is outstanding any more.
+// Encoding (gfx9 family): vmcnt[3:0] in bits 3:0 and vmcnt[5:4] in bits 15:14; expcnt (bits 6:4) and lgkmcnt
+// (bits 11:8) stay at their maxima, which means no wait on them.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
 // A 64-bit LDS read that transposes 16-bit elements inside each group of 16

@@ -16,6 +16,8 @@ struct AttendArgs {
   int64_t arena_tokens;      // rows per batch entry of each arena
   const HeadWork* work;      // device [H]: the layer's heads by descending run length, each with its run
   int max_len;               // longest run among the H heads (host copy)
+  int uniform_len = -1;      // >= 0: all H runs have this length and lie back to back from row uniform_row0 in
+  int uniform_row0 = 0;      //       head order; the bf16 kernel then needs no table read (the fp32 one ignores it)
   const void *q, *k_cur, *v_cur, *k_arena, *v_arena;
   void* out;
   float sm_scale;

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv,
   };
   auto step = [&](int it, auto buf_tag) {
     constexpr int buf = decltype(buf_tag)::value;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vmcnt<0>();
     __syncthreads();
     issue(it + 2, buf, 0);
     issue(it + 1, buf ^ 1, 1);
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv,
     step(it, std::integral_constant<int, 0>{});
     step(it + 1, std::integral_constant<int, 1>{});
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  wait_vmcnt<0>();
   float acc = l_run + m_run;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256, 2) void probe_tile_stream_kernel(const char* s
   issue(0);
   unsigned acc = 0;
   for (int t = 0; t < steps; ++t) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vmcnt<0>();
     __syncthreads();
     if (t + 1 < steps) issue(t + 1);
     acc ^= *reinterpret_cast<const unsigned*>(&lds[t & 1][tid * 4]);

@@ -117,7 +117,7 @@ def test_more_scales_than_the_abi_takes_are_rejected():
 
 
 def test_layout_is_a_valid_fifo_and_respects_the_budget_accounting():
-    for name in ["layer2b", "stack2b", "stack8b"]:
+    for name in ["layer2b", "stack2b", "stack8b", "serving"]:
         cfg = hi.CONFIGS[name]
         L, H, s = cfg["L"], cfg["H"], cfg["sinks"]
         t0 = hi.tokens_per_scale(cfg["sides"])

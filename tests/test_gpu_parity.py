@@ -417,6 +417,44 @@ def test_rank_dispersion_over_gpu_calibration_runs():
     assert got.max() <= 0.25 * L * H
 
 
+def test_rank_positions_from_gpu_beta_against_oracle_beta_are_reported(capsys):
+    # Rankings are compared bit-exactly on identical beta bytes elsewhere.  Here the two betas differ: the GPU's
+    # (bf16 products, fp32 sums) and the oracle's (fp64), both for one 2B-like layer at full size (16 heads, 13
+    # scales, both batch rows as data points).  Masses must agree to 1e-4; how many rank positions of the orders
+    # O_i and of the CAS order then differ is printed, not gated: near-ties may flip.
+    cfg = hi.CONFIGS["layer2b"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    c = hi.cumulative_tokens(t0)
+    K, L, H, d, s, nb = len(t0), 1, cfg["H"], cfg["d"], cfg["sinks"], cfg["batch"]
+    sm = 1.0 / np.sqrt(d)
+    w = hi.head_weights(61, L, H, K)
+    q, k, _ = hi.make_qkv(61, 0, cfg, w=w)
+    dq, dk = _dev(q, k)
+    shape = hk.Shape(L, H, d, t0, nb, "bf16")
+    beta = torch.zeros(L, H, K, K, device="cuda")
+    qs = [dq[:, :, c[i] - t0[i]:c[i]].contiguous() for i in range(K)]
+    ks = [dk[:, :, :c[i]].contiguous() for i in range(K)]
+    ws = torch.empty(hk.binding.calibrate_scales_workspace_bytes(shape, list(range(K))), dtype=torch.uint8, device="cuda")
+    hk.heatkv_calibrate_scales_accumulate(shape, 0, list(range(K)), qs, ks, sm, 1.0 / nb, beta, None, ws)
+    torch.cuda.synchronize()
+    beta_gpu = beta.cpu().numpy()
+    t1 = orc.one_based(t0)
+    beta_orc = np.zeros((L, H, K, K))
+    for h in range(H):
+        for b in range(nb):
+            beta_orc[0, h] += orc.beta_matrix(q[b, h].double().numpy(), k[b, h].double().numpy(), t1, sm)[1:, 1:] / nb
+    assert np.abs(beta_gpu - beta_orc).max() <= 1e-4
+    og = orc.head_orders(orc.beta_one_based(beta_gpu), L, H, K, s)
+    oo = orc.head_orders(orc.beta_one_based(beta_orc.astype(np.float32)), L, H, K, s)
+    differ = {i: sum(a != b for a, b in zip(og[i], oo[i])) for i in og}
+    cg = orc.cas_order(orc.beta_one_based(beta_gpu), L, H, K, s)
+    co = orc.cas_order(orc.beta_one_based(beta_orc.astype(np.float32)), L, H, K, s)
+    with capsys.disabled():
+        print(f"\n[rank positions] GPU beta vs oracle beta, one 2B-like layer (T = {L * H}): max |beta diff| "
+              f"{np.abs(beta_gpu - beta_orc).max():.2e}; positions that differ per source scale "
+              f"{differ} (of {L * H} each), CAS order {sum(a != b for a, b in zip(cg, co))}", flush=True)
+
+
 def test_binding_rejects_wrong_shapes_and_dtypes_on_device():
     t0 = hi.tokens_per_scale(hi.SIDES_TINY)
     shape = hk.Shape(1, 4, 64, t0, 1, "f32")
