@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--stack-passes", default="both", choices=["both", "generation", "batched"],
                     help="stack workloads only: generation-order passes (attention + update fused, per-image time), "
                          "scale-batched passes (per-scale kernel durations of attention and update), or both")
+    ap.add_argument("--fp8-cache", action="store_true",
+                    help="stack workloads only: report the run with the cache rows stored as FP8 E4M3 codes "
+                         "(same token budget, half the cache bytes); the native-format run is kept under native_cache")
     ap.add_argument("--no-stack-20x", action="store_true",
                     help="default workload only: skip the two 20x stacks that supply the per-image attention time")
     ap.add_argument("--no-mfma-probe", action="store_true",
@@ -294,12 +297,15 @@ def main():
     if not args.no_stack_20x and not args.attend_only:
         del ka, va, q_s, k_s, v_s, kall_s, out_s, dq, dk, dv
         torch.cuda.empty_cache()
-        stacks = {name: stack_measure(name, dev, passes=2, warmup=1) for name in ("stack8b", "serving")}
+        stacks = {name: stack_measure(name, dev, passes=2, warmup=1, fp8_cache=(name == "serving"))
+                  for name in ("stack8b", "serving")}
         result["per_image_attention_ms_at_20x"] = {name: r["ms_per_image"] for name, r in stacks.items()}
         result["stacks_20x"] = stacks
         result["roofline_hbm"] = hbm_leg(stacks["serving"])
         result["roofline_mfma_large_scales"] = mfma_leg(stacks["serving"])
         result["append_kernel"] = append_leg(stacks["serving"])
+        # the same serving stack with the cache rows stored as FP8 E4M3 (same tokens kept, half the cache bytes)
+        result["roofline_hbm_fp8_cache"] = hbm_leg(stacks["serving"]["fp8_cache"], "serving_small_scales_fp8_cache")
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -398,7 +404,10 @@ def run_stack(args, dev):
     """--workload stack2b / stack8b / serving: the stack measurement alone, as one JSON line (profiling aid)."""
     r = stack_measure(args.workload, dev, passes=args.steps, warmup=args.warmup,
                       generation=args.stack_passes in ("both", "generation"),
-                      batched=args.stack_passes in ("both", "batched"))
+                      batched=args.stack_passes in ("both", "batched"), fp8_cache=args.fp8_cache)
+    if args.fp8_cache:  # report the 8-bit cache run, keep the native one beside it
+        native = {k: v for k, v in r.items() if k != "fp8_cache"}
+        r = dict(r["fp8_cache"], native_cache=native)
     value = r.get("attend_tflops_generation_order")
     result = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -412,7 +421,7 @@ def run_stack(args, dev):
     }
     if r.get("per_scale"):
         result["roofline"] = mfma_leg(r)
-        result["roofline_hbm"] = hbm_leg(r)
+        result["roofline_hbm"] = hbm_leg(r, "serving_small_scales_fp8_cache" if args.fp8_cache else "serving_small_scales")
         result["append_kernel"] = append_leg(r)
     if not args.no_mfma_probe:
         result["mfma_probe"] = mfma_probe(dev)
@@ -420,7 +429,7 @@ def run_stack(args, dev):
     print(json.dumps(result))
 
 
-def stack_measure(name, dev, passes, warmup, generation=True, batched=True):
+def stack_measure(name, dev, passes, warmup, generation=True, batched=True, fp8_cache=False):
     """One 20x stack (stack8b: one image with its CFG row; serving: 16 images), every layer with activations of
     its own (nothing a launch reads was touched by the launches just before it, so K/V, Q and the current scale
     come from HBM, not from L2 or the memory-side cache).  Two kinds of passes:
@@ -429,7 +438,9 @@ def stack_measure(name, dev, passes, warmup, generation=True, batched=True):
       * scale-batched (for every scale: the L attention launches back to back between one event pair, then the
         L cache-update launches between another): average duration per launch of either kernel at every scale,
         hence TFLOP/s, KV GB/s and the copy bandwidth of the update.  Legal because an update only retires its own
-        layer's region of the scale, which only that layer's attention reads, and the updates keep their order."""
+        layer's region of the scale, which only that layer's attention reads, and the updates keep their order.
+    fp8_cache: the same passes once more over the same activations with the cache rows stored as FP8 E4M3 codes
+    (same token budget, half the cache bytes), reported under "fp8_cache"."""
     import torch
 
     import heatkv_inputs as hi
@@ -446,8 +457,6 @@ def stack_measure(name, dev, passes, warmup, generation=True, batched=True):
     w = hi.head_weights(0, L, H, K)
     beta = hi.expected_beta_from_weights(w, t0).astype(np.float32)
     shape = hk.Shape(L, H, d, t0, nb, cfg["dtype"])
-    plan = hk.heatkv_build_schedule(shape, beta, B * 2 * d * esz, s)
-    plan.upload()
     sl = [slice(c[i] - t0[i], c[i]) for i in range(K)]
     acts = []  # acts[l][kk] = (q, k, v, out)
     for l in range(L):
@@ -455,85 +464,104 @@ def stack_measure(name, dev, passes, warmup, generation=True, batched=True):
         acts.append([(q[:, :, sl[i]].contiguous(), k[:, :, sl[i]].contiguous(), v[:, :, sl[i]].contiguous(),
                       torch.empty_like(q[:, :, sl[i]])) for i in range(K)])
         del q, k, v
-    ka = torch.zeros(max(plan.arena_bytes, 16), dtype=torch.uint8, device=dev)
-    va = torch.zeros_like(ka)
-    flops, byts, app_rows = np.zeros(K), np.zeros(K), np.zeros(K)
-    for kk in range(K):
-        for l in range(L):
-            n = nb * int((plan.runs(kk, l)[1].astype(np.int64) + t0[kk]).sum())
-            flops[kk] += 4.0 * t0[kk] * d * n
-            byts[kk] += 2.0 * row * (n + nb * H * t0[kk])
-            if kk + 1 < K:  # rows the update writes: the whole region the next scale reads
-                app_rows[kk] += nb * int(plan.runs(kk + 1, l)[1].astype(np.int64).sum())
 
-    def generation_pass():
+    def measure(kv_format):
+        kv_row = d * (1 if kv_format == hk.KV_FP8_E4M3 else esz)  # bytes of a cached K (or V) row
+        plan = hk.heatkv_build_schedule(shape, beta, B * 2 * kv_row, s, kv_format=kv_format)
+        plan.upload()
+        assert plan.budget_tokens == B
+        ka = torch.zeros(max(plan.arena_bytes, 16), dtype=torch.uint8, device=dev)
+        va = torch.zeros_like(ka)
+        flops, byts, app_bytes = np.zeros(K), np.zeros(K), np.zeros(K)
         for kk in range(K):
             for l in range(L):
-                q, k, v, o = acts[l][kk]
-                hk.heatkv_attend_append_scale(plan, l, kk, q, k, v, ka, va, sm, o)
+                n_prior = nb * int(plan.runs(kk, l)[1].astype(np.int64).sum())
+                n_cur = nb * H * t0[kk]
+                flops[kk] += 4.0 * t0[kk] * d * (n_prior + n_cur)
+                # K and V of the retained rows (cache format) and of the current scale, Q in, O out
+                byts[kk] += 2.0 * kv_row * n_prior + 2.0 * row * n_cur + 2.0 * row * n_cur
+                if kk + 1 < K:
+                    # the update writes the whole region the next scale reads (K and V); it reads the rows kept from
+                    # the old region in the cache format and the new scale's rows in the tensor dtype
+                    nxt = nb * int(plan.runs(kk + 1, l)[1].astype(np.int64).sum())
+                    ids = [plan.retained(kk + 1, l, h) for h in range(H)]
+                    new_rows = nb * sum(t0[kk] for h in range(H) if len(ids[h]) and ids[h][-1] == c[kk] - 1)
+                    app_bytes[kk] += 2.0 * (kv_row * nxt + kv_row * (nxt - new_rows) + row * new_rows)
 
-    def batched_pass(ev_att, ev_app):
+        def generation_pass():
+            for kk in range(K):
+                for l in range(L):
+                    q, k, v, o = acts[l][kk]
+                    hk.heatkv_attend_append_scale(plan, l, kk, q, k, v, ka, va, sm, o)
+
+        def batched_pass(ev_att, ev_app):
+            for kk in range(K):
+                ev_att[kk][0].record()
+                for l in range(L):
+                    q, k, v, o = acts[l][kk]
+                    hk.heatkv_attend_scale(plan, l, kk, q, k, v, ka, va, sm, o)
+                ev_att[kk][1].record()
+                ev_app[kk][0].record()
+                for l in range(L):
+                    q, k, v, o = acts[l][kk]
+                    hk.heatkv_append_scale(plan, l, kk, k, v, ka, va)
+                ev_app[kk][1].record()
+
+        out = {
+            "workload": f"{name}: {L} layers x {H} heads x d{d} {cfg['dtype']}, batch {nb}, {K} scales, "
+                        f"{cfg['factor']}x budget, sinks {s}; per-layer activations ({L} distinct sets)"
+                        + ("; cache rows stored as FP8 E4M3" if kv_format == hk.KV_FP8_E4M3 else ""),
+            "passes": passes, "images_per_pass": max(nb // 2, 1),
+            "kv_cache_mb": round(2 * plan.arena_bytes / 1e6, 1),
+            "arena_tokens_over_budget": round(plan.arena_tokens / B, 4), "launches_per_scale": L,
+        }
+        if generation:
+            for _ in range(warmup):
+                generation_pass()
+            torch.cuda.synchronize()
+            t_start = time.perf_counter()
+            for _ in range(passes):
+                generation_pass()
+            torch.cuda.synchronize()
+            ms_per_pass = (time.perf_counter() - t_start) * 1e3 / passes
+            out.update({"ms_per_pass": round(ms_per_pass, 3), "ms_per_image": round(ms_per_pass / max(nb // 2, 1), 3),
+                        "attend_tflops_generation_order": round(float(flops.sum()) / ms_per_pass / 1e9, 1)})
+        if not batched:
+            return out
+        mk = lambda: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+        evs = [(mk(), mk()) for _ in range(passes)]
+        if not generation:
+            for _ in range(warmup):
+                batched_pass(mk(), mk())
+        for ea, ep in evs:
+            batched_pass(ea, ep)
+        torch.cuda.synchronize()
+        att_us = np.array([[a.elapsed_time(b) for a, b in ea] for ea, _ in evs]).mean(0) * 1e3 / L
+        app_us = np.array([[a.elapsed_time(b) for a, b in ep] for _, ep in evs]).mean(0) * 1e3 / L
+        rows = []
         for kk in range(K):
-            ev_att[kk][0].record()
-            for l in range(L):
-                q, k, v, o = acts[l][kk]
-                hk.heatkv_attend_scale(plan, l, kk, q, k, v, ka, va, sm, o)
-            ev_att[kk][1].record()
-            ev_app[kk][0].record()
-            for l in range(L):
-                q, k, v, o = acts[l][kk]
-                hk.heatkv_append_scale(plan, l, kk, k, v, ka, va)
-            ev_app[kk][1].record()
-
-    out = {
-        "workload": f"{name}: {L} layers x {H} heads x d{d} {cfg['dtype']}, batch {nb}, {K} scales, "
-                    f"{cfg['factor']}x budget, sinks {s}; per-layer activations ({L} distinct sets)",
-        "passes": passes, "images_per_pass": max(nb // 2, 1),
-        "arena_tokens_over_budget": round(plan.arena_tokens / B, 4), "launches_per_scale": L,
-    }
-    if generation:
-        for _ in range(warmup):
-            generation_pass()
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(passes):
-            generation_pass()
-        torch.cuda.synchronize()
-        ms_per_pass = (time.perf_counter() - t_start) * 1e3 / passes
-        out.update({"ms_per_pass": round(ms_per_pass, 3), "ms_per_image": round(ms_per_pass / max(nb // 2, 1), 3),
-                    "attend_tflops_generation_order": round(float(flops.sum()) / ms_per_pass / 1e9, 1)})
-    if not batched:
+            fl, by, ab = flops[kk] / L, byts[kk] / L, app_bytes[kk] / L  # per launch
+            rows.append({
+                "k": kk, "t": t0[kk], "attend_us": round(float(att_us[kk]), 2),
+                "tflops": round(fl / att_us[kk] / 1e6, 1),
+                "pct_mfma_peak": round(100 * fl / att_us[kk] / 1e6 / PEAK_BF16_TFLOPS, 2),
+                "kv_mb": round(by / 1e6, 2), "kv_gbs": round(by / att_us[kk] / 1e3, 1),
+                "pct_hbm_peak": round(100 * by / att_us[kk] / 1e3 / PEAK_HBM_GBS, 2),
+                "flop_per_byte": round(fl / by, 1),
+                "append_us": round(float(app_us[kk]), 2), "append_mb": round(ab / 1e6, 2),
+                "append_gbs": round(ab / app_us[kk] / 1e3, 1) if kk + 1 < K else None,
+            })
+        out.update({"attend_ms_per_pass_kernel_only": round(float(att_us.sum()) * L / 1e3, 3),
+                    "append_ms_per_pass_kernel_only": round(float(app_us.sum()) * L / 1e3, 3), "per_scale": rows})
         return out
 
-    mk = lambda: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
-    evs = [(mk(), mk()) for _ in range(passes)]
-    if not generation:
-        for _ in range(warmup):
-            batched_pass(mk(), mk())
-    for ea, ep in evs:
-        batched_pass(ea, ep)
-    torch.cuda.synchronize()
-    att_us = np.array([[a.elapsed_time(b) for a, b in ea] for ea, _ in evs]).mean(0) * 1e3 / L
-    app_us = np.array([[a.elapsed_time(b) for a, b in ep] for _, ep in evs]).mean(0) * 1e3 / L
-    rows = []
-    for kk in range(K):
-        fl, by = flops[kk] / L, byts[kk] / L  # per launch
-        ab = 2.0 * 2.0 * row * app_rows[kk] / L  # K and V rows, each read once and written once
-        rows.append({
-            "k": kk, "t": t0[kk], "attend_us": round(float(att_us[kk]), 2),
-            "tflops": round(fl / att_us[kk] / 1e6, 1), "pct_mfma_peak": round(100 * fl / att_us[kk] / 1e6 / PEAK_BF16_TFLOPS, 2),
-            "kv_mb": round(by / 1e6, 2), "kv_gbs": round(by / att_us[kk] / 1e3, 1),
-            "pct_hbm_peak": round(100 * by / att_us[kk] / 1e3 / PEAK_HBM_GBS, 2),
-            "flop_per_byte": round(fl / by, 1),
-            "append_us": round(float(app_us[kk]), 2), "append_mb": round(ab / 1e6, 2),
-            "append_gbs": round(ab / app_us[kk] / 1e3, 1) if kk + 1 < K else None,
-        })
-    out.update({"attend_ms_per_pass_kernel_only": round(float(att_us.sum()) * L / 1e3, 3),
-                "append_ms_per_pass_kernel_only": round(float(app_us.sum()) * L / 1e3, 3), "per_scale": rows})
-    return out
+    result = measure(hk.KV_NATIVE)
+    if fp8_cache:
+        result["fp8_cache"] = measure(hk.KV_FP8_E4M3)
+    return result
 
 
-def hbm_leg(stack):
+def hbm_leg(stack, traffic_key="serving_small_scales"):
     """Second leg of the headline metric: KV GB/s of the attention launches bound by the K/V read: scales of at
     most 256 tokens (arithmetic intensity 22-172 FLOP/B, under the chip's ridge of 312) whose launch moves at
     least 16 MB; on the serving stack those are the scales of 36, 64, 144 and 256 tokens."""
@@ -545,7 +573,7 @@ def hbm_leg(stack):
     gbs = by / us / 1e3
     return {"kernel": "attend_bf16_d128_kernel", "workload": stack["workload"], "bound": "hbm",
             "launches": [r["t"] for r in rows], "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": measured_traffic("serving_small_scales"),
+            "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": measured_traffic(traffic_key),
             "algorithmic_bytes_per_launch": round(by / max(len(rows), 1)),
             "avg_launch_us": round(us / max(len(rows), 1), 2),
             "per_scale": [{k: r[k] for k in ("t", "attend_us", "kv_mb", "kv_gbs", "pct_hbm_peak", "tflops",

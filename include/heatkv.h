@@ -64,6 +64,17 @@ extern "C" {
 
 #define HEATKV_MAX_SCALES 31
 
+/* Storage format of the cache rows in the arenas.  NATIVE: the shape's dtype.  FP8_E4M3 (bf16 shapes with d = 128
+ * only): every retained K and V element is stored as one OCP FP8 E4M3 code (1 sign, 4 exponent bits with bias 7,
+ * 3 mantissa bits, subnormals, no infinities, largest magnitude 448), rounded to nearest with ties to even and
+ * saturating at +-448 when a scale is appended (a NaN stays a NaN); no scale factors.  The paper leaves
+ * quantisation of the cache to future work (Sec. 5) and fixes no format; this one halves the bytes of a cached
+ * token (2*d instead of 4*d for K and V together).  Rows are converted once, when they enter the cache; later
+ * cache updates move the codes unchanged.  Attention reads them back exactly (every E4M3 value is a bf16 value);
+ * the current scale's K/V, which come from the caller's tensors, keep their precision. */
+#define HEATKV_KV_NATIVE 0
+#define HEATKV_KV_FP8_E4M3 1
+
 /* Problem shape (Sec. 3.1 notation): L layers, H heads per layer, head dimension d,
  * K scales with t[k] tokens each, `batch` independent sequences processed together. */
 typedef struct {
@@ -155,6 +166,13 @@ int heatkv_calibrate_scales_accumulate(const heatkv_shape* shape, int layer, int
 int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t budget_bytes_per_seq,
                           int sinks, int variant, heatkv_plan** out);
 
+/* heatkv_build_schedule with a storage format for the cache rows (HEATKV_KV_*).  The token budget follows the
+ * format: B = floor(bytes / (2*d*kv_elem_size)), kv_elem_size = 1 for HEATKV_KV_FP8_E4M3, so the same byte budget
+ * holds twice the tokens.  heatkv_build_schedule is this call with HEATKV_KV_NATIVE.  HEATKV_EINVAL for an
+ * unknown format or one the shape does not support. */
+int heatkv_build_schedule_kv(const heatkv_shape* shape, const float* beta, uint64_t budget_bytes_per_seq,
+                             int sinks, int variant, int kv_format, heatkv_plan** out);
+
 /* Plan from an explicit retention pattern instead of Alg. 1.
  * present host uint8 [K][L][H][K]: present[k][l][h][i] != 0 iff prior scale i
  * is in head (l,h)'s cache when scale k is generated.  Requirements, else
@@ -162,6 +180,8 @@ int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t
  * scale k stays absent at k+1.  No G/E/A sets, orders or N_k are defined for
  * such a plan (the accessors return HEATKV_EINVAL). */
 int heatkv_load_schedule(const heatkv_shape* shape, const uint8_t* present, heatkv_plan** out);
+/* The same with a storage format for the cache rows (HEATKV_KV_*). */
+int heatkv_load_schedule_kv(const heatkv_shape* shape, const uint8_t* present, int kv_format, heatkv_plan** out);
 
 void heatkv_plan_destroy(heatkv_plan* plan);
 
@@ -185,9 +205,12 @@ int heatkv_plan_sets(const heatkv_plan* plan, int k, int which, uint8_t* bitmap)
  * head (layer,head) holds when scale k is generated, ascending.  token_idx may
  * be null to query the count; *n receives the count. */
 int heatkv_plan_retained(const heatkv_plan* plan, int k, int layer, int head, int32_t* token_idx, int32_t* n);
+/* Storage format of the plan's cache rows (HEATKV_KV_*). */
+int heatkv_plan_kv_format(const heatkv_plan* plan);
 /* Rows per batch entry of each arena. */
 int64_t heatkv_plan_arena_tokens(const heatkv_plan* plan);
-/* Bytes of one arena (K or V): batch * arena_tokens * d * elem_size. */
+/* Bytes of one arena (K or V): batch * arena_tokens * d * (size of a stored element: that of the dtype, or 1 for
+ * HEATKV_KV_FP8_E4M3). */
 size_t heatkv_plan_arena_bytes(const heatkv_plan* plan);
 /* Run table seen by attend_scale(layer,k): for each head the first arena row
  * (within one batch entry) and the number of retained prior tokens.

@@ -7,6 +7,8 @@ memory handles and for the current HIP stream.
 """
 from .binding import (  # noqa: F401
     HeatKVError,
+    KV_FP8_E4M3,
+    KV_NATIVE,
     Plan,
     Shape,
     VARIANT_BINARY,
@@ -19,12 +21,14 @@ from .binding import (  # noqa: F401
     heatkv_attend_append_scale,
     heatkv_attend_scale,
     heatkv_build_schedule,
+    heatkv_build_schedule_kv,
     heatkv_calibrate,
     heatkv_calibrate_accumulate,
     heatkv_calibrate_scales_accumulate,
     heatkv_calibrate_static,
     heatkv_head_scores,
     heatkv_load_schedule,
+    heatkv_load_schedule_kv,
     heatkv_rank_dispersion,
     library_path,
 )

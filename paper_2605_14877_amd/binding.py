@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libheatkv.so")
 F32, BF16 = 0, 1
 VARIANT_HEATKV, VARIANT_BINARY, VARIANT_NAIVE, VARIANT_BINARY_NAIVE = 0, 1, 2, 3
 SET_G, SET_E, SET_A = 0, 1, 2
+KV_NATIVE, KV_FP8_E4M3 = 0, 1
 _DTYPES = {"f32": F32, "bf16": BF16}
 
 
@@ -71,6 +72,12 @@ def lib():
     L.heatkv_build_schedule.argtypes = [sp, f32p, C.c_uint64, C.c_int, C.c_int, C.POINTER(vp)]
     L.heatkv_load_schedule.restype = C.c_int
     L.heatkv_load_schedule.argtypes = [sp, u8p, C.POINTER(vp)]
+    L.heatkv_build_schedule_kv.restype = C.c_int
+    L.heatkv_build_schedule_kv.argtypes = [sp, f32p, C.c_uint64, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    L.heatkv_load_schedule_kv.restype = C.c_int
+    L.heatkv_load_schedule_kv.argtypes = [sp, u8p, C.c_int, C.POINTER(vp)]
+    L.heatkv_plan_kv_format.restype = C.c_int
+    L.heatkv_plan_kv_format.argtypes = [vp]
     L.heatkv_plan_destroy.restype = None
     L.heatkv_plan_destroy.argtypes = [vp]
     L.heatkv_plan_upload.restype = C.c_int
@@ -218,6 +225,10 @@ class Plan:
         return int(lib().heatkv_plan_budget_tokens(self.handle))
 
     @property
+    def kv_format(self):
+        return int(lib().heatkv_plan_kv_format(self.handle))
+
+    @property
     def arena_tokens(self):
         return int(lib().heatkv_plan_arena_tokens(self.handle))
 
@@ -264,21 +275,37 @@ class Plan:
         return int(lib().heatkv_attend_workspace_bytes(self.handle, layer, k))
 
 
-def heatkv_build_schedule(shape, beta, budget_bytes_per_seq, sinks, variant=VARIANT_HEATKV):
+def heatkv_build_schedule(shape, beta, budget_bytes_per_seq, sinks, variant=VARIANT_HEATKV, kv_format=KV_NATIVE):
+    """kv_format != KV_NATIVE goes through heatkv_build_schedule_kv."""
     beta = np.ascontiguousarray(beta, dtype=np.float32)
     assert beta.shape == (shape.L, shape.H, shape.K, shape.K)
     h = C.c_void_p()
-    _check(lib().heatkv_build_schedule(shape.ref, beta.ctypes.data_as(C.POINTER(C.c_float)),
-                                       int(budget_bytes_per_seq), int(sinks), int(variant), C.byref(h)))
+    bp = beta.ctypes.data_as(C.POINTER(C.c_float))
+    if kv_format == KV_NATIVE:
+        _check(lib().heatkv_build_schedule(shape.ref, bp, int(budget_bytes_per_seq), int(sinks), int(variant),
+                                           C.byref(h)))
+    else:
+        _check(lib().heatkv_build_schedule_kv(shape.ref, bp, int(budget_bytes_per_seq), int(sinks), int(variant),
+                                              int(kv_format), C.byref(h)))
     return Plan(h.value, shape)
 
 
-def heatkv_load_schedule(shape, present):
+heatkv_build_schedule_kv = heatkv_build_schedule
+
+
+def heatkv_load_schedule(shape, present, kv_format=KV_NATIVE):
     present = np.ascontiguousarray(present, dtype=np.uint8)
     assert present.shape == (shape.K, shape.L, shape.H, shape.K)
     h = C.c_void_p()
-    _check(lib().heatkv_load_schedule(shape.ref, present.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(h)))
+    pp = present.ctypes.data_as(C.POINTER(C.c_uint8))
+    if kv_format == KV_NATIVE:
+        _check(lib().heatkv_load_schedule(shape.ref, pp, C.byref(h)))
+    else:
+        _check(lib().heatkv_load_schedule_kv(shape.ref, pp, int(kv_format), C.byref(h)))
     return Plan(h.value, shape)
+
+
+heatkv_load_schedule_kv = heatkv_load_schedule
 
 
 def calibrate_workspace_bytes(shape, k1):

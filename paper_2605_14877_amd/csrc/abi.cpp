@@ -90,6 +90,15 @@ int check_plan_index(const heatkv_plan* p, int layer, int k) {
   return HEATKV_OK;
 }
 
+// 8-bit cache rows exist for the matrix-core attention path only (bf16, d = 128).
+int check_kv_format(const heatkv_plan* p, int kv_format) {
+  if (kv_format == HEATKV_KV_NATIVE) return HEATKV_OK;
+  if (kv_format != HEATKV_KV_FP8_E4M3) return fail(HEATKV_EINVAL, "unknown cache storage format");
+  if (p->dtype != HEATKV_BF16 || p->d != 128)
+    return fail(HEATKV_EINVAL, "HEATKV_KV_FP8_E4M3 needs a bf16 shape with head dimension 128");
+  return HEATKV_OK;
+}
+
 int finish_plan(heatkv_plan* p, heatkv_plan** out) {
   int rc = heatkv::derive_layout(p);
   if (rc) {
@@ -106,8 +115,8 @@ extern "C" {
 
 const char* heatkv_last_error(void) { return heatkv::last_error_cstr(); }
 
-int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t budget_bytes_per_seq, int sinks,
-                          int variant, heatkv_plan** out) {
+int heatkv_build_schedule_kv(const heatkv_shape* shape, const float* beta, uint64_t budget_bytes_per_seq, int sinks,
+                             int variant, int kv_format, heatkv_plan** out) {
   if (!out) return fail(HEATKV_EINVAL, "out is null");
   *out = nullptr;
   if (!beta) return fail(HEATKV_EINVAL, "beta is null");
@@ -116,6 +125,7 @@ int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t
   if (!p) return fail(HEATKV_ENOMEM, "out of host memory");
   int rc = heatkv::init_shape(p, shape);
   if (!rc && (sinks < 0 || sinks > p->K - 2)) rc = fail(HEATKV_EINVAL, "sinks must be in [0, K-2]");
+  if (!rc) rc = check_kv_format(p, kv_format);
   if (rc) {
     delete p;
     return rc;
@@ -123,7 +133,8 @@ int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t
   p->sinks = sinks;
   p->variant = variant;
   p->from_schedule = true;
-  p->B = int64_t(budget_bytes_per_seq / (2u * uint64_t(p->d) * p->elem_size()));
+  p->kv_format = kv_format;
+  p->B = int64_t(budget_bytes_per_seq / (2u * uint64_t(p->d) * p->kv_elem_size()));
   try {
     rc = heatkv::build_sets(p, beta);
     if (rc) {
@@ -137,17 +148,24 @@ int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t
   }
 }
 
-int heatkv_load_schedule(const heatkv_shape* shape, const uint8_t* present, heatkv_plan** out) {
+int heatkv_build_schedule(const heatkv_shape* shape, const float* beta, uint64_t budget_bytes_per_seq, int sinks,
+                          int variant, heatkv_plan** out) {
+  return heatkv_build_schedule_kv(shape, beta, budget_bytes_per_seq, sinks, variant, HEATKV_KV_NATIVE, out);
+}
+
+int heatkv_load_schedule_kv(const heatkv_shape* shape, const uint8_t* present, int kv_format, heatkv_plan** out) {
   if (!out) return fail(HEATKV_EINVAL, "out is null");
   *out = nullptr;
   if (!present) return fail(HEATKV_EINVAL, "present is null");
   heatkv_plan* p = new (std::nothrow) heatkv_plan;
   if (!p) return fail(HEATKV_ENOMEM, "out of host memory");
   int rc = heatkv::init_shape(p, shape);
+  if (!rc) rc = check_kv_format(p, kv_format);
   if (rc) {
     delete p;
     return rc;
   }
+  p->kv_format = kv_format;
   try {
     rc = heatkv::load_pattern(p, present);
     if (rc) {
@@ -160,6 +178,12 @@ int heatkv_load_schedule(const heatkv_shape* shape, const uint8_t* present, heat
     return fail(HEATKV_ENOMEM, "out of host memory");
   }
 }
+
+int heatkv_load_schedule(const heatkv_shape* shape, const uint8_t* present, heatkv_plan** out) {
+  return heatkv_load_schedule_kv(shape, present, HEATKV_KV_NATIVE, out);
+}
+
+int heatkv_plan_kv_format(const heatkv_plan* plan) { return plan ? plan->kv_format : HEATKV_KV_NATIVE; }
 
 void heatkv_plan_destroy(heatkv_plan* plan) {
   if (!plan) return;
@@ -224,7 +248,7 @@ int64_t heatkv_plan_arena_tokens(const heatkv_plan* plan) { return plan ? plan->
 
 size_t heatkv_plan_arena_bytes(const heatkv_plan* plan) {
   if (!plan) return 0;
-  return size_t(plan->batch) * size_t(plan->arena_tokens) * size_t(plan->d) * plan->elem_size();
+  return size_t(plan->batch) * size_t(plan->arena_tokens) * size_t(plan->d) * plan->kv_elem_size();
 }
 
 int heatkv_plan_runs(const heatkv_plan* plan, int k, int layer, int32_t* row_out, int32_t* len_out) {
@@ -255,6 +279,7 @@ int heatkv_append_scale(heatkv_plan* plan, int layer, int k, const void* k_new, 
   if ((rc = ensure_uploaded(plan))) return rc;
   heatkv::AppendArgs a{};
   a.row_bytes = int(plan->d * plan->elem_size());
+  a.kv_fp8 = plan->kv_format == HEATKV_KV_FP8_E4M3;
   a.batch = plan->batch;
   a.H = plan->H;
   a.t_k = plan->t[k];
@@ -296,6 +321,7 @@ int attend_impl(heatkv_plan* plan, int layer, int k, const void* q, const void* 
   if ((rc = ensure_uploaded(plan))) return rc;
   heatkv::AttendArgs a{};
   a.dtype = plan->dtype;
+  a.kv_fp8 = plan->kv_format == HEATKV_KV_FP8_E4M3;
   a.d = plan->d;
   a.H = plan->H;
   a.batch = plan->batch;

@@ -20,6 +20,7 @@ hipError_t launch_append(const AppendArgs& a, hipStream_t stream) {
   if (a.row_bytes % 16 != 0) return hipErrorInvalidValue;
   CopyParams p{};
   p.chunks_per_row = a.row_bytes / 16;
+  p.kv_fp8 = a.kv_fp8 ? 1 : 0;
   p.H = a.H;
   p.t_k = a.t_k;
   p.arena_tokens = a.arena_tokens;

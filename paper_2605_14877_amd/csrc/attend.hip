@@ -79,13 +79,23 @@ extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 // stream with its own pair of tile stages (128 KB of dynamic LDS), and at the end stream 1 hands its partial
 // output, row sums and references to stream 0 through LDS.  The unit then runs two wavefronts per SIMD, as it
 // does when two workgroups share it, without a second pass over HBM.
-template <int KS>
+//
+// FP8: the arenas hold FP8 E4M3 codes, 128 bytes per row (single-stream instance only).  A tile of the retained run
+// lands as it is (8 KB) in a landing buffer behind the tile stages, one for K and one for V, and at the top of the
+// step that first needs it the whole workgroup rewrites it as a bf16 tile in its stage (exact: every E4M3 value is
+// a bf16 value), with one more barrier; from there on the step is the same.  Current-scale tiles are bf16 and go
+// straight to their stage.  80 KB of LDS per workgroup: two workgroups still share a compute unit.
+template <int KS, bool FP8>
 __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_kernel(AttendParams p) {
   static_assert(KS == 1 || KS == 2, "one or two key streams");
-  __shared__ __attribute__((aligned(1024))) char lds_static[KS == 1 ? 2 : 1][2][KS == 1 ? TILE_BYTES : 16];
-  // [stream * 2 + stage][K,V]; 64 KB are static, 128 KB exceed the static limit and come as dynamic LDS
-  char(*lds)[2][TILE_BYTES] = KS == 1 ? reinterpret_cast<char(*)[2][TILE_BYTES]>(&lds_static[0][0][0])
-                                      : reinterpret_cast<char(*)[2][TILE_BYTES]>(attend_dynamic_lds);
+  static_assert(!(FP8 && KS == 2), "the 8-bit cache path has one key stream");
+  constexpr bool kStaticLds = KS == 1 && !FP8;
+  __shared__ __attribute__((aligned(1024))) char lds_static[kStaticLds ? 2 : 1][2][kStaticLds ? TILE_BYTES : 16];
+  // [stream * 2 + stage][K,V]; 64 KB are static, anything more exceeds the static limit and comes as dynamic LDS
+  char(*lds)[2][TILE_BYTES] = kStaticLds ? reinterpret_cast<char(*)[2][TILE_BYTES]>(&lds_static[0][0][0])
+                                         : reinterpret_cast<char(*)[2][TILE_BYTES]>(attend_dynamic_lds);
+  char* const raw_k = reinterpret_cast<char*>(lds) + 4 * TILE_BYTES;  // FP8 only: landing buffers, 8 KB each
+  char* const raw_v = raw_k + tile::RAW8_BYTES;
 
   if (static_cast<int>(blockIdx.x) >= p.attend_blocks) {  // fused append: a plain row copy by 256 lanes
     const int j = blockIdx.x - p.attend_blocks;
@@ -121,9 +131,11 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
 
   const int t_k = p.t_k;
   const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D128;
-  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + run_row) * D128;
-  const char* k_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_arena) + run_off);
-  const char* v_prior = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_arena) + run_off);
+  constexpr int PRIOR_ROW_BYTES = FP8 ? tile::RAW8_ROW_BYTES : ROW_BYTES;
+  constexpr int PRIOR_TILE_BYTES = BN * PRIOR_ROW_BYTES;
+  const long long run_off = (static_cast<long long>(b) * p.arena_tokens + run_row) * PRIOR_ROW_BYTES;
+  const char* k_prior = static_cast<const char*>(p.k_arena) + run_off;
+  const char* v_prior = static_cast<const char*>(p.v_arena) + run_off;
   const char* k_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.k_cur) + cur_off);
   const char* v_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_cur) + cur_off);
 
@@ -181,6 +193,10 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
+    if (FP8 && prior) {  // codes land in the K landing buffer; the step that needs the tile converts it
+      tile::issue_raw8(lds_base + 4 * TILE_BYTES, wave, lane, left, k_prior + static_cast<long long>(local) * PRIOR_TILE_BYTES);
+      return;
+    }
     const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
     const unsigned kd = lds_base + buf * (2 * TILE_BYTES);
     // Two separate statements under a workgroup-uniform branch: the full-tile path has no per-lane arithmetic.
@@ -194,6 +210,11 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     const bool prior = it >= tiles_cur;
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
+    if (FP8 && prior) {
+      tile::issue_raw8(lds_base + 4 * TILE_BYTES + tile::RAW8_BYTES, wave, lane, left,
+                       v_prior + static_cast<long long>(local) * PRIOR_TILE_BYTES);
+      return;
+    }
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
     const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES;
     if (left >= BN)
@@ -296,6 +317,15 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   auto pipe_step = [&](int j, auto kb1, auto vb0, f32x16 (&s_in)[2], f32x16 (&s_out)[2]) {
     wait_vmcnt<0>();
     __syncthreads();
+    if constexpr (FP8) {
+      // What this step reads and arrived as codes: K(j+1), fetched during step j-1 into the K landing buffer, and
+      // V(j) likewise.  Their stages are free (last read in step j-2), the landing buffers are free again after
+      // the barrier, before this step's copies go out.
+      const bool ck = j + 1 < tiles_all && j + 1 >= tiles_cur, cv = j >= tiles_cur;
+      if (ck) tile::convert_raw8<false>(raw_k, lds[decltype(kb1)::value][0], tid);
+      if (cv) tile::convert_raw8<true>(raw_v, lds[decltype(vb0)::value][1], tid);
+      if (ck || cv) __syncthreads();
+    }
     if (j + 2 < steps_all && has_tile(j + 2)) issue_k(j + 2, decltype(vb0)::value);  // K stage j & 1: read by step j-1
     // V stage (j+1) & 1 likewise; the single-stream prologue has already fetched V(1)
     if ((KS == 2 || j > 0) && has_tile(j + 1)) issue_v(j + 1, decltype(kb1)::value);
@@ -315,7 +345,11 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     if (tiles_all > 1) {
       issue_k(1, 1);
       issue_v(1, 1);
-      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+      // younger than K(0): V(0) and tile 1, four copies per wavefront and bf16 tile, two per 8-bit tile
+      if (FP8 && tiles_cur == 1)
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     }
@@ -346,6 +380,15 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   // Epilogue: the last tile has scores but no successor.
   wait_vmcnt<0>();
   __syncthreads();
+  if constexpr (FP8) {
+    if (it >= tiles_cur) {  // V of the last tile is still in its landing buffer
+      if (it & 1)
+        tile::convert_raw8<true>(raw_v, lds[1][1], tid);
+      else
+        tile::convert_raw8<true>(raw_v, lds[0][1], tid);
+      __syncthreads();
+    }
+  }
   if (KS == 1 && !active) return;
   if (active && has_tile(it)) {
     if (it & 1)
@@ -519,6 +562,7 @@ size_t attend_workspace_bytes(int, int, int, int, int, int) { return 0; }
 namespace {
 
 constexpr int TWO_STREAM_LDS_BYTES = 2 * 2 * 2 * TILE_BYTES;  // two streams x two stages x (K, V)
+constexpr int FP8_LDS_BYTES = 2 * 2 * TILE_BYTES + 2 * tile::RAW8_BYTES;  // two stages x (K, V) + two landing buffers
 constexpr int TWO_STREAM_MAX_BLOCKS = 256;                    // compute units of the chip
 constexpr int TWO_STREAM_MIN_TOKENS = 384;                    // shorter walks gain nothing (measured at 256)
 
@@ -529,8 +573,11 @@ hipError_t allow_two_stream_lds() {
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && (done.load(std::memory_order_acquire) >> dev & 1)) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_d128_kernel<2>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_d128_kernel<2, false>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, TWO_STREAM_LDS_BYTES);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_d128_kernel<1, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FP8_LDS_BYTES);
   if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
   return e;
 }
@@ -560,6 +607,7 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
   if (a.ndesc > 0) {
     if (a.row_bytes % 16 != 0) return hipErrorInvalidValue;
     p.copy.chunks_per_row = a.row_bytes / 16;
+    p.copy.kv_fp8 = a.kv_fp8 ? 1 : 0;
     p.copy.H = a.H;
     p.copy.t_k = a.t_k;
     p.copy.arena_tokens = a.arena_tokens;
@@ -576,15 +624,20 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
     const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
     p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
     const dim3 grid(unsigned(p.attend_blocks) + copy_blocks);
-    // At most one workgroup per compute unit: two key streams per workgroup put two wavefronts on every SIMD.
-    if (p.attend_blocks <= TWO_STREAM_MAX_BLOCKS && a.t_k >= TWO_STREAM_MIN_TOKENS) {
+    if (a.kv_fp8) {  // 8-bit cache rows: the single-stream instance with landing buffers
       const hipError_t e = allow_two_stream_lds();
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(attend_bf16_d128_kernel<2>, grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
+      hipLaunchKernelGGL((attend_bf16_d128_kernel<1, true>), grid, dim3(256), FP8_LDS_BYTES, stream, p);
+    } else if (p.attend_blocks <= TWO_STREAM_MAX_BLOCKS && a.t_k >= TWO_STREAM_MIN_TOKENS) {
+      // At most one workgroup per compute unit: two key streams per workgroup put two wavefronts on every SIMD.
+      const hipError_t e = allow_two_stream_lds();
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((attend_bf16_d128_kernel<2, false>), grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
     } else {
-      hipLaunchKernelGGL(attend_bf16_d128_kernel<1>, grid, dim3(256), 0, stream, p);
+      hipLaunchKernelGGL((attend_bf16_d128_kernel<1, false>), grid, dim3(256), 0, stream, p);
     }
   } else {
+    if (a.kv_fp8) return hipErrorInvalidValue;
     p.n_qtiles = (a.t_k + FQ - 1) / FQ;
     p.attend_blocks = int(unsigned(p.n_qtiles) * a.H * a.batch);
     const dim3 grid(unsigned(p.attend_blocks) + copy_blocks);

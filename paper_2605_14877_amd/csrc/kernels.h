@@ -12,6 +12,7 @@ namespace heatkv {
 
 struct AttendArgs {
   int dtype, d, H, batch;
+  bool kv_fp8 = false;       // arena rows are FP8 E4M3 codes (d bytes per row) instead of the dtype's
   int t_k;                   // queries (= current-scale keys) per head
   int64_t arena_tokens;      // rows per batch entry of each arena
   const HeadWork* work;      // device [H]: the layer's heads by descending run length, each with its run
@@ -35,7 +36,8 @@ size_t attend_workspace_bytes(int dtype, int d, int H, int batch, int t_k, int m
 hipError_t launch_attend(const AttendArgs& a, hipStream_t stream);
 
 struct AppendArgs {
-  int row_bytes;             // d * elem_size
+  int row_bytes;             // d * elem_size of the new scale's tensors
+  bool kv_fp8 = false;       // arena rows are FP8 E4M3 codes: rows from the new scale are converted on the way in
   int batch, H, t_k;
   int64_t arena_tokens;
   const CopyDesc* descs;     // device

@@ -42,6 +42,7 @@ struct DeviceTables {
 struct heatkv_plan {
   // shape
   int32_t L = 0, H = 0, d = 0, K = 0, batch = 0, dtype = 0, sinks = 0, variant = 0;
+  int32_t kv_format = HEATKV_KV_NATIVE;  // how the arenas store a row
   int32_t T = 0;
   bool from_schedule = false;  // false: built from an explicit retention pattern
   std::vector<int32_t> t, c;   // c[k] = t[0]+..+t[k]
@@ -72,6 +73,7 @@ struct heatkv_plan {
   heatkv::DeviceTables dev;
 
   size_t elem_size() const { return dtype == HEATKV_BF16 ? 2 : 4; }
+  size_t kv_elem_size() const { return kv_format == HEATKV_KV_FP8_E4M3 ? 1 : elem_size(); }
   size_t idx(int k, int l, int h) const { return (static_cast<size_t>(k) * L + l) * H + h; }
   size_t idx(int k, int l) const { return static_cast<size_t>(k) * L + l; }
 };

@@ -77,6 +77,48 @@ __device__ __forceinline__ void issue_ragged(unsigned lds_tile, int wave, int la
   }
 }
 
+// 8-bit cache rows (FP8 E4M3 codes, 128 bytes per row): a 64-row tile is 8 KB and lands in LDS as it lies in
+// memory, 2 KB per wavefront in two copies; `left` < 64: rows past the end re-read the last valid row.
+constexpr int RAW8_ROW_BYTES = 128;
+constexpr int RAW8_BYTES = ROWS * RAW8_ROW_BYTES;
+__device__ __forceinline__ void issue_raw8(unsigned lds_tile, int wave, int lane, int left, const char* src) {
+  if (left >= ROWS) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) copy_1k(lds_tile + wave * 2048 + j * 1024, lane * 16, src + wave * 2048 + j * 1024);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int row = 16 * wave + 8 * j + (lane >> 3);
+      const int rr = row < left ? row : left - 1;
+      copy_1k_ragged(lds_tile + wave * 2048 + j * 1024, rr * RAW8_ROW_BYTES + (lane & 7) * 16, src);
+    }
+  }
+}
+// Turns a landed 8-bit tile (`raw`, LDS) into the bf16 tile format at `stage` (LDS): 256 lanes, four groups of
+// eight codes each; every E4M3 value is a bf16 value, so the conversion is exact.  SWZ_V selects the V swizzle.
+template <bool SWZ_V>
+__device__ __forceinline__ void convert_raw8(const char* raw, char* stage, int tid) {
+  // The per-lane offsets below are cheap; made opaque here so that they are recomputed on the spot instead of being
+  // kept in registers across the caller's tile loop, which has none to spare.
+  asm volatile("" : "+v"(tid));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = tid + 256 * i;
+    const int row = idx >> 4, lc = idx & 15;
+    const uint2 w = *reinterpret_cast<const uint2*>(raw + row * RAW8_ROW_BYTES + lc * 8);
+    union {
+      bf16x2 h[4];
+      uint4 u;
+    } o;
+    o.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(w.x), 1.0f, false);
+    o.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(w.x), 1.0f, true);
+    o.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(w.y), 1.0f, false);
+    o.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(static_cast<int>(w.y), 1.0f, true);
+    const int pc = lc ^ (SWZ_V ? swizzle_v(row) : swizzle_k(row));
+    *reinterpret_cast<uint4*>(stage + row * ROW_BYTES + (pc << 4)) = o.u;
+  }
+}
+
 // Reader offsets inside a tile for the 32x32x16 MFMA operand layouts (lane = n + 32 hl, n = lane % 32).
 // K as the A operand of S^T = K Q^T: row n (+32 per column block), chunk 2 ks + hl for ks = 0..7.
 __device__ __forceinline__ void reader_off_k(int lane, int (&k_off)[8]) {

@@ -405,3 +405,27 @@ def test_calibrate_static_rejects_what_does_not_fit_before_any_gpu_call():
     assert rc == -1 and b"exceed the static workspace" in binding.lib().heatkv_last_error()
     fits = hk.Shape(1, 16, 128, t0, 32, "bf16")
     assert binding.calibrate_workspace_bytes(fits, 12) <= (1 << 20)
+
+
+def test_8_bit_cache_format_doubles_the_tokens_a_byte_budget_holds():
+    cfg = hi.CONFIGS["layer2b"]
+    t0 = hi.tokens_per_scale(cfg["sides"])
+    beta0, _ = harness.config_beta("layer2b")
+    shape = hk.Shape(1, cfg["H"], 128, t0, 2, "bf16")
+    B = hi.budget_tokens(cfg)
+    native = hk.heatkv_build_schedule(shape, beta0, B * 512, 3)
+    same_tokens = hk.heatkv_build_schedule(shape, beta0, B * 256, 3, kv_format=hk.KV_FP8_E4M3)
+    same_bytes = hk.heatkv_build_schedule(shape, beta0, B * 512, 3, kv_format=hk.KV_FP8_E4M3)
+    assert native.kv_format == hk.KV_NATIVE and same_tokens.kv_format == hk.KV_FP8_E4M3
+    assert native.budget_tokens == same_tokens.budget_tokens == B and same_bytes.budget_tokens == 2 * B
+    # the schedule is a function of the token budget alone: same sets, same rows, half the bytes
+    assert native.N().tolist() == same_tokens.N().tolist() and native.arena_tokens == same_tokens.arena_tokens
+    assert same_tokens.arena_bytes * 2 == native.arena_bytes
+    for k in range(len(t0)):
+        assert np.array_equal(native.sets(k, binding.SET_A), same_tokens.sets(k, binding.SET_A))
+    assert sum(same_bytes.N().tolist()) < sum(native.N().tolist())  # twice the tokens: fewer heads pruned
+    for bad in (dict(shape=hk.Shape(1, 4, 64, t0[:4], 1, "f32"), fmt=hk.KV_FP8_E4M3), dict(shape=shape, fmt=5)):
+        with pytest.raises(hk.HeatKVError) as e:
+            hk.heatkv_build_schedule(bad["shape"], harness.random_beta(0, bad["shape"].L, bad["shape"].H, bad["shape"].K),
+                                     1 << 20, 1, kv_format=bad["fmt"])
+        assert e.value.code == -1
