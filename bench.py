@@ -272,7 +272,7 @@ def main():
         "arena_tokens_over_budget": round(plan.arena_tokens / max(B, 1), 4),
         "per_scale": per_scale,
         "roofline": {
-            "kernel": "attend_bf16_d128_kernel",
+            "kernel": "attend_bf16_kernel",
             "bound": "mfma",
             "achieved": round(att_tflops, 2),
             "peak": PEAK_BF16_TFLOPS,
@@ -571,7 +571,7 @@ def hbm_leg(stack, traffic_key="serving_small_scales"):
     by = sum(r["kv_mb"] for r in rows) * 1e6
     us = sum(r["attend_us"] for r in rows)
     gbs = by / us / 1e3
-    return {"kernel": "attend_bf16_d128_kernel", "workload": stack["workload"], "bound": "hbm",
+    return {"kernel": "attend_bf16_kernel", "workload": stack["workload"], "bound": "hbm",
             "launches": [r["t"] for r in rows], "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": measured_traffic(traffic_key),
             "algorithmic_bytes_per_launch": round(by / max(len(rows), 1)),
@@ -587,7 +587,7 @@ def mfma_leg(stack):
         return None
     fl = sum(r["tflops"] * r["attend_us"] for r in rows)
     us = sum(r["attend_us"] for r in rows)
-    return {"kernel": "attend_bf16_d128_kernel", "workload": stack["workload"], "bound": "mfma",
+    return {"kernel": "attend_bf16_kernel", "workload": stack["workload"], "bound": "mfma",
             "launches": [r["t"] for r in rows], "achieved": round(fl / us, 1), "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": round(fl / us / PEAK_BF16_TFLOPS, 4),
             "per_scale": [{k: r[k] for k in ("t", "attend_us", "tflops", "pct_mfma_peak")} for r in rows]}

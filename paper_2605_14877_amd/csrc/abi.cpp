@@ -314,8 +314,6 @@ int attend_impl(heatkv_plan* plan, int layer, int k, const void* q, const void* 
   if (max_len > 0 && (!k_arena || !v_arena)) return fail(HEATKV_EINVAL, "null arena pointer");
   const size_t need = heatkv::attend_workspace_bytes(plan->dtype, plan->d, plan->H, plan->batch, plan->t[k], max_len);
   if (need > 0 && (!ws || ws_bytes < need)) return fail(HEATKV_EINVAL, "attend workspace too small");
-  if (plan->dtype == HEATKV_BF16 && plan->d != 128)
-    return fail(HEATKV_EINVAL, "bf16 attention supports head dimension 128 only");
   const int ndesc = (with_append && k < plan->K - 1) ? plan->desc_count[plan->idx(k, layer)] : 0;
   if (ndesc > 0 && (!k_arena_rw || !v_arena_rw)) return fail(HEATKV_EINVAL, "null arena pointer");
   if ((rc = ensure_uploaded(plan))) return rc;
@@ -392,8 +390,6 @@ int calibrate_impl(const heatkv_shape* shape, int layer, int n_scales, const int
   if (layer < 0 || layer >= shape->L) return fail(HEATKV_EINVAL, "layer out of range");
   if (n_scales < 1 || n_scales > shape->K) return fail(HEATKV_EINVAL, "number of scales out of range");
   if (!k1 || !q || !k_all) return fail(HEATKV_EINVAL, "null argument array");
-  if (shape->dtype == HEATKV_BF16 && shape->d != 128)
-    return fail(HEATKV_EINVAL, "bf16 calibration supports head dimension 128 only");
   heatkv::CalibrateArgs a{};
   bool seen[HEATKV_MAX_SCALES] = {};
   for (int i = 0; i < n_scales; ++i) {

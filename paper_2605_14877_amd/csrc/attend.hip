@@ -41,7 +41,7 @@ struct AttendParams {
 };
 
 // ---------------------------------------------------------------------------
-// bf16, d = 128: matrix-core kernel.
+// bf16, d = 128 or 64: matrix-core kernel (the description takes d = 128: rows of 256 bytes).
 //
 // Workgroup = 4 wavefronts x 32 queries, two workgroups per compute unit.  The
 // keys of a head are walked in 64-row tiles, first the current scale (dense
@@ -67,9 +67,7 @@ struct AttendParams {
 // ---------------------------------------------------------------------------
 constexpr int BM = 128;              // queries per workgroup
 constexpr int BN = tile::ROWS;       // keys per tile
-constexpr int D128 = 128;
-constexpr int ROW_BYTES = tile::ROW_BYTES;
-constexpr int TILE_BYTES = tile::BYTES;
+constexpr int TILE_BYTES_D128 = tile::BYTES;  // 64 rows x 256 bytes
 
 extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 
@@ -85,10 +83,18 @@ extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 // step that first needs it the whole workgroup rewrites it as a bf16 tile in its stage (exact: every E4M3 value is
 // a bf16 value), with one more barrier; from there on the step is the same.  Current-scale tiles are bf16 and go
 // straight to their stage.  80 KB of LDS per workgroup: two workgroups still share a compute unit.
-template <int KS, bool FP8>
-__global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_kernel(AttendParams p) {
+//
+// D: head dimension, 128 or 64 (rows of 256 or 128 bytes, tiles of 16 or 8 KB, 8 or 4 MFMA steps per score block and
+// 4 or 2 accumulator blocks; the single-stream, bf16-cache instance only).
+template <int KS, bool FP8, int D>
+__global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(AttendParams p) {
   static_assert(KS == 1 || KS == 2, "one or two key streams");
   static_assert(!(FP8 && KS == 2), "the 8-bit cache path has one key stream");
+  static_assert(D == 128 || (D == 64 && KS == 1 && !FP8), "d = 64: single stream, bf16 cache rows");
+  constexpr int ROW_BYTES = 2 * D;            // one bf16 row
+  constexpr int TILE_BYTES = BN * ROW_BYTES;  // 16 KB (d = 128) or 8 KB (d = 64)
+  constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per row
+  constexpr int NK = D / 16, NV = D / 32;     // MFMA steps of a score block, accumulator blocks of 32 columns
   constexpr bool kStaticLds = KS == 1 && !FP8;
   __shared__ __attribute__((aligned(1024))) char lds_static[kStaticLds ? 2 : 1][2][kStaticLds ? TILE_BYTES : 16];
   // [stream * 2 + stage][K,V]; 64 KB are static, anything more exceeds the static limit and comes as dynamic LDS
@@ -130,7 +136,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   }
 
   const int t_k = p.t_k;
-  const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D128;
+  const long long cur_off = (static_cast<long long>(b) * p.H + h) * t_k * D;
   constexpr int PRIOR_ROW_BYTES = FP8 ? tile::RAW8_ROW_BYTES : ROW_BYTES;
   constexpr int PRIOR_TILE_BYTES = BN * PRIOR_ROW_BYTES;
   const long long run_off = (static_cast<long long>(b) * p.arena_tokens + run_row) * PRIOR_ROW_BYTES;
@@ -141,12 +147,12 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
 
   // Q as B operand: lane (n, hl) holds Q[row][16*ks + 8*hl .. +7] for ks = 0..7.
   const int q_row = qt * BM + wave * 32 + n;
-  bf16x8 qreg[8];
+  bf16x8 qreg[NK];
   {
     const int ld = q_row < t_k ? q_row : t_k - 1;
-    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + cur_off + static_cast<long long>(ld) * D128 + 8 * hl;
+    const bf16_t* qp = static_cast<const bf16_t*>(p.q) + cur_off + static_cast<long long>(ld) * D + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < NK; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
 
   // Tile schedule: tiles [0, tiles_cur) cover the current scale, the rest the retained run.
@@ -161,17 +167,17 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   // instructions (tile::issue_full / issue_ragged): the compiler then does not see an LDS store it would have to
   // order against the tile reads of the other buffer (it would wait for the whole prefetch in the middle of the
   // math).  Ordering is explicit instead: s_waitcnt vmcnt(0) and the workgroup barrier at the top of every step.
-  const int ld_off_k = tile::loader_off_k(wave, lane);
-  const int ld_off_v = tile::loader_off_v(wave, lane);
+  const int ld_off_k = tile::loader_off_k<ROW_BYTES>(wave, lane);
+  const int ld_off_v = tile::loader_off_v<ROW_BYTES>(wave, lane);
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<unsigned long long>(
       (__attribute__((address_space(3))) char*)(&lds[0][0][0]))) + g * (4 * TILE_BYTES);
-  int k_off[8], v_off[4];
-  tile::reader_off_k(lane, k_off);
-  tile::reader_off_v(lane, v_off);
+  int k_off[NK], v_off[NV];
+  tile::reader_off_k<ROW_BYTES>(lane, k_off);
+  tile::reader_off_v<ROW_BYTES>(lane, v_off);
 
-  f32x16 o[4];
+  f32x16 o[NV];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < NV; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
@@ -201,9 +207,9 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     const unsigned kd = lds_base + buf * (2 * TILE_BYTES);
     // Two separate statements under a workgroup-uniform branch: the full-tile path has no per-lane arithmetic.
     if (left >= BN)
-      tile::issue_full(kd, wave, ld_off_k, kb);
+      tile::issue_full<ROW_BYTES>(kd, wave, ld_off_k, kb);
     else
-      tile::issue_ragged<false>(kd, wave, lane, left, kb);
+      tile::issue_ragged<false, ROW_BYTES>(kd, wave, lane, left, kb);
   };
   auto issue_v = [&](int j, int buf) {
     const int it = KS * j + g;
@@ -218,9 +224,9 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
     const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES;
     if (left >= BN)
-      tile::issue_full(vd, wave, ld_off_v, vb);
+      tile::issue_full<ROW_BYTES>(vd, wave, ld_off_v, vb);
     else
-      tile::issue_ragged<true>(vd, wave, lane, left, vb);
+      tile::issue_ragged<true, ROW_BYTES>(vd, wave, lane, left, vb);
   };
 
   // S^T = K Q^T for the 64 keys of the K tile in buffer `buf` x this wavefront's 32 queries.
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < NK; ++ks)
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[ks]);
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
       m_run = m_new;
       l_run *= alpha;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < NV; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
     }
@@ -286,9 +292,9 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
 #pragma unroll
     for (int chunk = 0; chunk < 4; ++chunk) {
       const int cb = chunk >> 1, ks = chunk & 1;
-      VOperand va[4];
+      VOperand va[NV];
 #pragma unroll
-      for (int dblk = 0; dblk < 4; ++dblk) {
+      for (int dblk = 0; dblk < NV; ++dblk) {
         const char* base = vt + 16 * chunk * ROW_BYTES + v_off[dblk];
         va[dblk].s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
         va[dblk].s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
 #pragma unroll
       for (int j = 0; j < 4; ++j) l_run = __builtin_amdgcn_fdot2_f32_bf16(pb.h[j], ones, l_run, false);
 #pragma unroll
-      for (int dblk = 0; dblk < 4; ++dblk)
+      for (int dblk = 0; dblk < NV; ++dblk)
         o[dblk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dblk].v, pb.v, o[dblk], 0, 0, 0);
     }
   };
@@ -337,21 +343,22 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
 
   // Prologue: all four tile stages are free, so K(0), V(0), K(1) and V(1) all go out at once: one memory round
   // trip before the loop, and a walk of two tiles (every scale of up to 64 tokens) never waits for memory again.
-  // Loads return in issue order, so waiting until at most the twelve younger copies are outstanding means that
-  // K(0) has landed; tile 0 is a current-scale tile, whose address does not depend on the head's run.
+  // Loads return in issue order, so waiting until only the copies younger than K(0) are outstanding means that
+  // K(0) has landed (CPT copies per wavefront and bf16 tile, two per 8-bit tile); tile 0 is a current-scale tile,
+  // whose address does not depend on the head's run.
+  constexpr int CPT = TILE_BYTES / 4096;
   if (KS == 1) {
     issue_k(0, 0);
     issue_v(0, 0);
     if (tiles_all > 1) {
       issue_k(1, 1);
       issue_v(1, 1);
-      // younger than K(0): V(0) and tile 1, four copies per wavefront and bf16 tile, two per 8-bit tile
       if (FP8 && tiles_cur == 1)
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        wait_vmcnt<CPT + 4>();
       else
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        wait_vmcnt<3 * CPT>();
     } else {
-      asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      wait_vmcnt<CPT>();
     }
   } else {  // a stream may have no tile at all, or one: everything it has goes out, then a full wait
     if (has_tile(0)) issue_k(0, 0);
@@ -426,25 +433,26 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_d128_ke
   const float inv = 1.f / l_tot;
   // Output through LDS.  A lane owns one query row but only 4 consecutive columns at a time, so direct stores
   // would be 8-byte pieces scattered over 32 rows.  The K buffers are idle by now (their last reader passed the
-  // barrier above and no copy is in flight), so every wavefront stages its 32 x 128 tile in 8 KB of them, with
-  // the 16-byte chunks XORed with the row number, and writes it out as whole 256-byte rows, 1 KB per instruction.
-  char* stage = lds[wave >> 1][0] + (wave & 1) * 8192;
+  // barrier above and no copy is in flight), so every wavefront stages its 32 x d tile in half a K stage, with the
+  // 16-byte chunks XORed with the row number, and writes it out as whole rows, 1 KB per instruction.
+  char* stage = lds[wave >> 1][0] + (wave & 1) * (32 * ROW_BYTES);
 #pragma unroll
-  for (int dblk = 0; dblk < 4; ++dblk)
+  for (int dblk = 0; dblk < NV; ++dblk)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       bf16x4 v;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
-      *reinterpret_cast<bf16x4*>(stage + n * ROW_BYTES + (((4 * dblk + g) ^ (n & 15)) << 4) + 8 * hl) = v;
+      *reinterpret_cast<bf16x4*>(stage + n * ROW_BYTES + (((4 * dblk + g) ^ (n & (CPR - 1))) << 4) + 8 * hl) = v;
     }
   const int out_row0 = qt * BM + wave * 32;
-  bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(out_row0) * D128;
+  bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(out_row0) * D;
+  constexpr int ROWS_PER_STORE = 64 / CPR;  // CPR lanes write one row
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int row = 4 * r + (lane >> 4), slot = lane & 15;
-    const uint4 v = *reinterpret_cast<const uint4*>(stage + row * ROW_BYTES + ((slot ^ (row & 15)) << 4));
-    if (out_row0 + row < t_k) *reinterpret_cast<uint4*>(op + row * D128 + slot * 8) = v;
+  for (int r = 0; r < 32 / ROWS_PER_STORE; ++r) {
+    const int row = ROWS_PER_STORE * r + lane / CPR, slot = lane & (CPR - 1);
+    const uint4 v = *reinterpret_cast<const uint4*>(stage + row * ROW_BYTES + ((slot ^ (row & (CPR - 1))) << 4));
+    if (out_row0 + row < t_k) *reinterpret_cast<uint4*>(op + row * D + slot * 8) = v;
   }
 }
 
@@ -561,8 +569,8 @@ size_t attend_workspace_bytes(int, int, int, int, int, int) { return 0; }
 
 namespace {
 
-constexpr int TWO_STREAM_LDS_BYTES = 2 * 2 * 2 * TILE_BYTES;  // two streams x two stages x (K, V)
-constexpr int FP8_LDS_BYTES = 2 * 2 * TILE_BYTES + 2 * tile::RAW8_BYTES;  // two stages x (K, V) + two landing buffers
+constexpr int TWO_STREAM_LDS_BYTES = 2 * 2 * 2 * TILE_BYTES_D128;  // two streams x two stages x (K, V)
+constexpr int FP8_LDS_BYTES = 2 * 2 * TILE_BYTES_D128 + 2 * tile::RAW8_BYTES;  // two stages x (K, V) + two landing buffers
 constexpr int TWO_STREAM_MAX_BLOCKS = 256;                    // compute units of the chip
 constexpr int TWO_STREAM_MIN_TOKENS = 384;                    // shorter walks gain nothing (measured at 256)
 
@@ -573,10 +581,10 @@ hipError_t allow_two_stream_lds() {
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && (done.load(std::memory_order_acquire) >> dev & 1)) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_d128_kernel<2, false>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<2, false, 128>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, TWO_STREAM_LDS_BYTES);
   if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_d128_kernel<1, true>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<1, true, 128>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FP8_LDS_BYTES);
   if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
   return e;
@@ -619,22 +627,25 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
     copy_blocks = unsigned(a.ndesc) * a.batch;
   }
   if (a.dtype == HEATKV_BF16) {
-    if (a.d != 128) return hipErrorInvalidValue;
+    if (a.d != 128 && a.d != 64) return hipErrorInvalidValue;
+    if (a.d == 64 && a.kv_fp8) return hipErrorInvalidValue;
     p.n_qtiles = (a.t_k + BM - 1) / BM;
     const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
     p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
     const dim3 grid(unsigned(p.attend_blocks) + copy_blocks);
-    if (a.kv_fp8) {  // 8-bit cache rows: the single-stream instance with landing buffers
+    if (a.d == 64) {  // rows of 128 bytes: the single-stream instance
+      hipLaunchKernelGGL((attend_bf16_kernel<1, false, 64>), grid, dim3(256), 0, stream, p);
+    } else if (a.kv_fp8) {  // 8-bit cache rows: the single-stream instance with landing buffers
       const hipError_t e = allow_two_stream_lds();
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((attend_bf16_d128_kernel<1, true>), grid, dim3(256), FP8_LDS_BYTES, stream, p);
+      hipLaunchKernelGGL((attend_bf16_kernel<1, true, 128>), grid, dim3(256), FP8_LDS_BYTES, stream, p);
     } else if (p.attend_blocks <= TWO_STREAM_MAX_BLOCKS && a.t_k >= TWO_STREAM_MIN_TOKENS) {
       // At most one workgroup per compute unit: two key streams per workgroup put two wavefronts on every SIMD.
       const hipError_t e = allow_two_stream_lds();
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((attend_bf16_d128_kernel<2, false>), grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
+      hipLaunchKernelGGL((attend_bf16_kernel<2, false, 128>), grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
     } else {
-      hipLaunchKernelGGL((attend_bf16_d128_kernel<1, false>), grid, dim3(256), 0, stream, p);
+      hipLaunchKernelGGL((attend_bf16_kernel<1, false, 128>), grid, dim3(256), 0, stream, p);
     }
   } else {
     if (a.kv_fp8) return hipErrorInvalidValue;

@@ -55,7 +55,7 @@ __device__ __forceinline__ int scale_of_block(const CalibParams& p, int block) {
 }
 
 // ---------------------------------------------------------------------------
-// bf16, d = 128: S^T = K Q^T on the matrix cores, one lane per query column
+// bf16, d = 128 or 64: S^T = K Q^T on the matrix cores, one lane per query column
 // (same operand layout, LDS tile format and HBM -> LDS copy as the attention
 // kernel).  Two instances.  CSETS = 1: 128 queries per workgroup, one set of 32 per
 // wavefront, three workgroups per compute unit.  CSETS = 2: 256 queries per
@@ -70,18 +70,19 @@ __device__ __forceinline__ int scale_of_block(const CalibParams& p, int block) {
 // ---------------------------------------------------------------------------
 constexpr int CBM1 = 128;  // queries per set of four wavefronts
 constexpr int CBN = tile::ROWS;
-constexpr int CD = 128;
-constexpr int CROW_BYTES = tile::ROW_BYTES;
-constexpr int CTILE_BYTES = tile::BYTES;
 
 // Dynamic LDS: two K tiles, then blk_sum[k1+1][rows], blk_max[k1+1][rows], fin_max[rows] (floats), rows = the
 // queries of a workgroup.
-__host__ __device__ constexpr size_t calib_lds_bytes(int k1, int csets) {
-  return 2 * CTILE_BYTES + (2 * size_t(k1 + 1) + 1) * (CBM1 * csets) * sizeof(float);
+__host__ __device__ constexpr size_t calib_lds_bytes(int k1, int csets, int d) {
+  return 2 * size_t(CBN * 2 * d) + (2 * size_t(k1 + 1) + 1) * (CBM1 * csets) * sizeof(float);
 }
 
-template <int CSETS>
-__global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_kernel(CalibParams p) {
+template <int CSETS, int CD>
+__global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_kernel(CalibParams p) {
+  static_assert(CD == 128 || CD == 64, "head dimension 128 or 64");
+  constexpr int CROW_BYTES = 2 * CD;            // one bf16 row
+  constexpr int CTILE_BYTES = CBN * CROW_BYTES;  // 16 KB or 8 KB
+  constexpr int NK = CD / 16;                    // MFMA steps of a score block
   constexpr int CBM = CBM1 * CSETS;  // queries per workgroup
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const ScaleJob& job = p.job[scale_of_block(p, blockIdx.x)];
@@ -107,20 +108,20 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
                                                     static_cast<long long>(bh) * c_k1 * CD);
   // The second set of a tile exists only if the tile reaches past its first 128 rows (workgroup-uniform).
   const bool two_sets = CSETS == 2 && qt * CBM + 128 < t_k1;
-  bf16x8 qreg[CSETS][8];
+  bf16x8 qreg[CSETS][NK];
 #pragma unroll
   for (int qs = 0; qs < CSETS; ++qs) {
     const int q_row = qt * CBM + qs * 128 + wave * 32 + n;
     const int ld = q_row < t_k1 ? q_row : t_k1 - 1;
     const bf16_t* qp = static_cast<const bf16_t*>(job.q) + (static_cast<long long>(bh) * t_k1 + ld) * CD + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[qs][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < NK; ++ks) qreg[qs][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
   }
   const float c = p.sm_scale * kLog2e;
 
   // HBM -> LDS copy of one K tile in the tile format shared with the attention kernel (tile_lds.h: raw
   // global_load_lds, explicit ordering by s_waitcnt vmcnt + barrier).
-  const int ld_off = tile::loader_off_k(wave, lane);
+  const int ld_off = tile::loader_off_k<CROW_BYTES>(wave, lane);
   const unsigned lds_base =
       static_cast<unsigned>(reinterpret_cast<unsigned long long>((__attribute__((address_space(3))) char*)(&lds[0])));
   auto issue_tile = [&](int k2, int tile_i, int buf) {
@@ -128,12 +129,12 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
     const char* kb = kbase + static_cast<long long>(p.c[k2] - p.t[k2] + tile_i * CBN) * CROW_BYTES;
     const unsigned kd = lds_base + buf * CTILE_BYTES;
     if (left >= CBN)
-      tile::issue_full(kd, wave, ld_off, kb);
+      tile::issue_full<CROW_BYTES>(kd, wave, ld_off, kb);
     else  // ragged tile: rows past the end re-read the last valid row
-      tile::issue_ragged<false>(kd, wave, lane, left, kb);
+      tile::issue_ragged<false, CROW_BYTES>(kd, wave, lane, left, kb);
   };
-  int k_off[8];
-  tile::reader_off_k(lane, k_off);
+  int k_off[NK];
+  tile::reader_off_k<CROW_BYTES>(lane, k_off);
 
   float m_run[CSETS], cur[CSETS];
 #pragma unroll
@@ -154,9 +155,9 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
     if (nk2 <= k1) issue_tile(nk2, ntile, buf ^ 1);
     const char* kt = lds + buf * CTILE_BYTES;
 
-    bf16x8 ka[2][8];
+    bf16x8 ka[2][NK];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < NK; ++ks)
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb)
         ka[cb][ks] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * CROW_BYTES + k_off[ks]);
@@ -170,13 +171,13 @@ __global__ __launch_bounds__(256, CSETS == 1 ? 3 : 2) void calibrate_bf16_d128_k
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[cb][r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
+      for (int ks = 0; ks < NK; ++ks)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
           s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[cb][ks], qreg[qs][ks], s[cb], 0, 0, 0);
       if (qs == 0) {  // all sixteen operand reads go out before the first MFMA instead of two at a time
-        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NK, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NK, 0);
       }
 
       if (left < CBN) {
@@ -466,7 +467,7 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
       wide_blocks += (unsigned long long)((a.t[a.k1[i]] + 2 * CBM1 - 1) / (2 * CBM1)) * a.H * a.batch;
     if (wide_blocks >= 512) rows_per_block = 2 * CBM1;
   }
-  if (mfma && a.d != 128) return hipErrorInvalidValue;
+  if (mfma && a.d != 128 && a.d != 64) return hipErrorInvalidValue;
   if (!mfma && a.d != 64 && a.d != 128) return hipErrorInvalidValue;
   // Largest scale first: its workgroups are the long ones, the short ones then fill the gaps they leave.
   int order[MAXK];
@@ -498,15 +499,23 @@ hipError_t launch_calibrate(const CalibrateArgs& a, hipStream_t stream) {
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64 || !(raised.load(std::memory_order_acquire) >> dev & 1)) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&calibrate_bf16_d128_kernel<2>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, int(calib_lds_bytes(MAXK - 1, 2)));
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&calibrate_bf16_kernel<2, 128>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, int(calib_lds_bytes(MAXK - 1, 2, 128)));
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&calibrate_bf16_kernel<2, 64>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, int(calib_lds_bytes(MAXK - 1, 2, 64)));
       if (e != hipSuccess) return e;
       if (dev >= 0 && dev < 64) raised.fetch_or(1ull << dev, std::memory_order_release);
     }
-    if (rows_per_block == CBM1)
-      hipLaunchKernelGGL(calibrate_bf16_d128_kernel<1>, dim3(blocks), dim3(256), calib_lds_bytes(k1_max, 1), stream, p);
+    const size_t lds_bytes = calib_lds_bytes(k1_max, rows_per_block == CBM1 ? 1 : 2, a.d);
+    if (a.d == 128 && rows_per_block == CBM1)
+      hipLaunchKernelGGL((calibrate_bf16_kernel<1, 128>), dim3(blocks), dim3(256), lds_bytes, stream, p);
+    else if (a.d == 128)
+      hipLaunchKernelGGL((calibrate_bf16_kernel<2, 128>), dim3(blocks), dim3(256), lds_bytes, stream, p);
+    else if (rows_per_block == CBM1)
+      hipLaunchKernelGGL((calibrate_bf16_kernel<1, 64>), dim3(blocks), dim3(256), lds_bytes, stream, p);
     else
-      hipLaunchKernelGGL(calibrate_bf16_d128_kernel<2>, dim3(blocks), dim3(256), calib_lds_bytes(k1_max, 2), stream, p);
+      hipLaunchKernelGGL((calibrate_bf16_kernel<2, 64>), dim3(blocks), dim3(256), lds_bytes, stream, p);
   }
   else if (a.d == 64)
     hipLaunchKernelGGL(calibrate_f32_kernel<64>, dim3(blocks), dim3(256), 0, stream, p);

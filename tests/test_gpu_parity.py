@@ -123,11 +123,10 @@ def test_fp32_schedule_from_alg1_multi_layer(d, L, H, sides, s, den, batch):
         _check_all(outs[l], *qkv[l], t0, ref["present"], l, sm, TOL["f32"])
 
 
-def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None, fused=False):
+def _bf16_case(L, H, sides, s, den, batch, seed, sample_from=None, fused=False, d=128):
     t0 = hi.tokens_per_scale(sides)
     c = hi.cumulative_tokens(t0)
     K = len(t0)
-    d = 128
     sm = 1.0 / np.sqrt(d)
     cfg = dict(L=L, H=H, d=d, dtype="bf16", batch=batch, sides=sides)
     B = L * H * c[-2] // den
@@ -236,6 +235,15 @@ def test_bf16_two_key_streams_per_workgroup():
     _bf16_case(2, 3, (1, 3, 20, 22), 1, 2, 1, seed=22)
 
 
+def test_bf16_head_dimension_64():
+    # rows of 128 bytes: 8 KB tiles, four MFMA steps per score block, two accumulator blocks, its own swizzles.
+    # Ragged tails in both directions, several tiles per head, fused = separate, and 1024-token scales.
+    _bf16_case(1, 4, (1, 2, 4, 6, 8, 11, 13), 3, 3, 2, seed=81, d=64)
+    _bf16_case(2, 3, ((1, 2), (2, 3), (3, 6), (5, 10), (7, 13), (9, 19), (12, 23)), 2, 3, 2, seed=82, fused=True, d=64)
+    _bf16_case(1, 6, (1, 2, 4, 6, 8, 12, 16, 20, 24, 32), 3, 4, 2, seed=83, fused=True, d=64)
+    _bf16_case(1, 2, (1, 2, 4, 9, 20, 22), 2, 1, 1, seed=84, d=64)  # full budget: the longest runs
+
+
 def test_bf16_budget_extremes():
     # Full budget: nothing is pruned, every head walks all prior scales (the longest runs the layout can hold).
     # Smallest legal budget (the sink scales only): every head keeps just the sinks.  Both at sizes that use the
@@ -295,7 +303,8 @@ def test_bf16_layer2b_full_size():
 
 
 def test_calibrate_tiny_fp32_and_bf16_small():
-    for dtype, d, sides, batch, H in (("f32", 64, hi.SIDES_TINY, 1, 4), ("bf16", 128, (1, 2, 4, 6, 8, 12, 16), 2, 3)):
+    for dtype, d, sides, batch, H in (("f32", 64, hi.SIDES_TINY, 1, 4), ("bf16", 128, (1, 2, 4, 6, 8, 12, 16), 2, 3),
+                                      ("bf16", 64, (1, 2, 4, 6, 8, 12, 17), 2, 3)):
         t0 = hi.tokens_per_scale(sides)
         c = hi.cumulative_tokens(t0)
         K = len(t0)
