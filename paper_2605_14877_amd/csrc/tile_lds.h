@@ -62,16 +62,30 @@ __device__ __forceinline__ int loader_off_v(int wave, int lane) {
 // 16 * lane.  Raw instruction on purpose: when the compiler sees an LDS-writing load it orders every later LDS
 // read after it (a full wait in the middle of the math); here the ordering is the caller's s_waitcnt vmcnt +
 // workgroup barrier.  The instruction takes its LDS base from M0; the operand is bound to that register, so the
-// compiler writes M0 itself and knows that it did.  The leading s_nop is the wait state between a scalar write of
-// M0 and an LDS-DMA instruction that reads it (the compiler inserts it for its own such loads, not for text).
+// compiler writes M0 itself and knows that it did.
+// Two hazards that the compiler covers for its own instructions but not for text: an LDS-DMA instruction needs one
+// wait state after a scalar write of M0, and a vector-memory instruction must not read a scalar register within
+// five wait states of a vector-ALU write to it (v_readlane, which is how a spilled scalar comes back: seen for
+// the source address when scalar registers ran short).  The leading s_mov_b64 settles both: it is the instruction
+// between the M0 write and the copy, and the copy reads the address from the pair this scalar instruction wrote
+// (scalar-ALU results need no wait states before a vector-memory read, and a scalar instruction reading a
+// vector-written scalar register is interlocked by the hardware).
 __device__ __forceinline__ void copy_1k(unsigned lds_dst, int lane_off, const char* src) {
-  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(src), "{m0}"(lds_dst) : "memory");
+  unsigned long long base;
+  asm volatile("s_mov_b64 %0, %2\n\tglobal_load_lds_dwordx4 %1, %0"
+               : "=&s"(base)
+               : "v"(lane_off), "s"(src), "{m0}"(lds_dst)
+               : "memory");
 }
 // The same instruction under another text, for the ragged-tile path: the differing text keeps the compiler from
 // merging the two paths back into one statement with per-lane selected operands (24 vector instructions in
 // every step of the common path).
 __device__ __forceinline__ void copy_1k_ragged(unsigned lds_dst, int lane_off, const char* src) {
-  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\t; ragged" ::"v"(lane_off), "s"(src), "{m0}"(lds_dst) : "memory");
+  unsigned long long base;
+  asm volatile("s_mov_b64 %0, %2\n\tglobal_load_lds_dwordx4 %1, %0\n\t; ragged"
+               : "=&s"(base)
+               : "v"(lane_off), "s"(src), "{m0}"(lds_dst)
+               : "memory");
 }
 
 // This wavefront's copies of a full tile: `src` = first byte of the tile's 64 contiguous rows, `lds_tile` =
