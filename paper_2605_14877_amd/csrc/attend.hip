@@ -246,25 +246,9 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
         s[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[cb], 0, 0, 0);
       }
   };
-  // Masks the ragged tail of tile `it`, folds its row maxima into the running reference and, rarely,
+  // Folds the maximum of a tile's scores (this lane's 32 of them) into the running reference and, rarely,
   // rescales what has been accumulated so far.
-  auto settle = [&](int j, f32x16 (&s)[2]) {
-    const int it = KS * j + g;
-    const bool prior = it >= tiles_cur;
-    const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
-    if (left < BN) {  // workgroup-uniform and rare: kept a branch (the empty asm keeps it from becoming 32 selects)
-      asm volatile("; ragged tile mask" ::: "memory");
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (32 * cb + 8 * (r >> 2) + 4 * hl + (r & 3) >= left) s[cb][r] = -INFINITY;
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
+  auto raise = [&](float mx) {
     mx = max_halves(mx);
     if (__any(mx > m_run + slack_raw)) {
       const float m_new = fmaxf(m_run, mx);
@@ -276,6 +260,38 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
     }
+  };
+  auto lane_max = [&](const f32x16 (&s)[2]) {
+    float mx = s[0][0];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[cb][r]);
+    return mx;
+  };
+  // Masks the ragged tail of the stream's tile j (keys past the end of the scale or of the run get -inf);
+  // returns whether there was one.
+  auto mask_tail = [&](int j, f32x16 (&s)[2]) {
+    const int it = KS * j + g;
+    const bool prior = it >= tiles_cur;
+    const int left = (prior ? n_prior : t_k) - (prior ? it - tiles_cur : it) * BN;
+    if (left >= BN) return false;  // workgroup-uniform and rare: kept a branch
+    // Register r of block cb holds key 32 cb + 8 (r / 4) + r % 4 + 4 hl: compared as a compile-time constant
+    // against one per-lane limit, formed here and hidden from the optimiser so that it is not turned back into
+    // 32 per-lane key numbers that would live in registers across the whole tile loop (nor into 32 selects).
+    int lim = left - 4 * hl;
+    asm volatile("; ragged tile mask" : "+v"(lim)::"memory");
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (32 * cb + 8 * (r >> 2) + (r & 3) >= lim) s[cb][r] = -INFINITY;
+    return true;
+  };
+  // Masks the tail of tile j and folds its row maxima into the running reference.
+  auto settle = [&](int j, f32x16 (&s)[2]) {
+    mask_tail(j, s);
+    raise(lane_max(s));
   };
   // P^T = 2^(S^T c - m c) in bf16, 16 keys at a time, each chunk feeding O^T += V^T P^T at once.  The row
   // sum is taken over the rounded probabilities, pairwise, with the bf16 dot-product instruction.
@@ -313,6 +329,122 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
     }
   };
 
+  // The steady-state step in one piece: scores of the next tile into s_out, P V of this tile from s_in, with the
+  // order of issue fixed by hand.  Left to itself the compiler clusters the score MFMAs at the K reads that feed
+  // them, back to back, and the exponentials elsewhere; a wavefront issues in order, so an MFMA waiting for the
+  // matrix pipe holds back the vector work that could run in the shadow of the one before.  Here the step is a
+  // sequence of 32 slots, one MFMA each followed by its share of vector and LDS work; scheduling fences keep the
+  // slots apart and the MFMA at the head of its slot:
+  //   S(g), g = 0..3: the NK/4 K-steps of the score product that go with chunk g (both 32-key blocks)
+  //   A(g): P V for the 16 keys of chunk g (NV MFMAs)
+  //   order S(0) A(0) S(1) A(1) S(2) A(2) S(3) A(3).  P(0) is computed in the slots of S(0), P(g+1) in those of
+  //   A(g) and S(g+1), the row maxima of the new scores in those of A(3); the K operands of S(g+1) are read in the
+  //   slots of S(g), the V operands of A(g+1) in those of A(g): every operand a whole phase before its MFMA.
+  // Returns this lane's maximum over the new scores (before any tail mask).
+  auto step_math = [&](const f32x16 (&s_in)[2], f32x16 (&s_out)[2], const bf16x8 (&k0)[NK / 4][2],
+                       const bf16x8 (&v0)[NV], auto kb1, auto vb0) {
+    constexpr int KPC = NK / 4;          // K-steps per phase S
+    constexpr int NS = 2 * KPC;          // slots of a phase S
+    constexpr int NA = NV;               // slots of a phase A
+    constexpr int HALVES = 8;            // a chunk's probabilities come in 8 half units (one probability per lane each)
+    static_assert(HALVES % NS == 0 && HALVES % (NS + NA) == 0, "phases divide the vector work evenly");
+    const char* kt = lds[2 * g + decltype(kb1)::value][0];
+    const char* vt = lds[2 * g + decltype(vb0)::value][1];
+    const float mc = m_run * c;
+    bf16x8 kop[NK][2], vop[4][NV];
+    float e[4][8];
+    union {
+      bf16x8 v;
+      bf16x2 h[4];
+    } pb[4];
+    auto load_k = [&](int ks, int cb) {
+      kop[ks][cb] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[ks]);
+    };
+    auto load_v = [&](int chunk, int dblk) {
+      const char* base = vt + 16 * chunk * ROW_BYTES + v_off[dblk];
+      VOperand t;
+      t.s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
+      t.s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
+      vop[chunk][dblk] = t.v;
+    };
+    // Half unit u (0..7) of chunk `chunk`: one probability per lane; the odd ones also pack a pair and add it to
+    // the row sum.
+    auto p_half = [&](int chunk, int u) {
+      const int cb = chunk >> 1, r = 8 * (chunk & 1) + u;
+      e[chunk][u] = fast_exp2(fmaf(s_in[cb][r], c, -mc));
+      if (u & 1) {
+        pb[chunk].h[u >> 1] = bf16x2{static_cast<bf16_t>(e[chunk][u - 1]), static_cast<bf16_t>(e[chunk][u])};
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pb[chunk].h[u >> 1], ones, l_run, false);
+      }
+    };
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_out[cb][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < KPC; ++i)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) kop[i][cb] = k0[i][cb];
+#pragma unroll
+    for (int dblk = 0; dblk < NV; ++dblk) vop[0][dblk] = v0[dblk];
+    float mx = -INFINITY;
+    auto s_slot = [&](int gch, int i, int halves_chunk, int& half) {  // slot i of phase S(gch)
+      const int ks = gch * KPC + (i >> 1), cb = i & 1;
+      s_out[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks][cb], qreg[ks], s_out[cb], 0, 0, 0);
+      fence();
+      if (gch < 3) load_k(ks + KPC, cb);
+      const int n = gch == 0 ? HALVES / NS : HALVES / (NS + NA);
+      for (int u = 0; u < n; ++u) p_half(halves_chunk, half++);
+      fence();
+    };
+    int half = 0;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) s_slot(0, i, 0, half);
+#pragma unroll
+    for (int gch = 0; gch < 4; ++gch) {
+      half = 0;
+#pragma unroll
+      for (int d = 0; d < NA; ++d) {  // slot d of phase A(gch)
+        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[gch][d], pb[gch].v, o[d], 0, 0, 0);
+        fence();
+        if (gch < 3) {
+          load_v(gch + 1, d);
+#pragma unroll
+          for (int u = 0; u < HALVES / (NS + NA); ++u) p_half(gch + 1, half++);
+        } else {  // the new scores are complete: their maxima, 32 / NA registers per slot
+#pragma unroll
+          for (int r = d * (32 / NA); r < (d + 1) * (32 / NA); ++r) mx = fmaxf(mx, s_out[r >> 4][r & 15]);
+          asm volatile("" : "+v"(mx));  // keeps the partial maximum in this slot (it is only consumed on one branch later)
+        }
+        fence();
+      }
+      if (gch < 3) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) s_slot(gch + 1, i, gch + 1, half);
+      }
+    }
+    return mx;
+  };
+  // The first operands of a step (K-steps of phase S(0), V blocks of phase A(0)): read right after the barrier,
+  // before the step's tile copies are issued, so that their LDS round trip passes under the scalar work of issuing.
+  auto preload = [&](bf16x8 (&k0)[NK / 4][2], bf16x8 (&v0)[NV], auto kb1, auto vb0) {
+    const char* kt = lds[2 * g + decltype(kb1)::value][0];
+    const char* vt = lds[2 * g + decltype(vb0)::value][1];
+#pragma unroll
+    for (int i = 0; i < NK / 4; ++i)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) k0[i][cb] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[i]);
+#pragma unroll
+    for (int dblk = 0; dblk < NV; ++dblk) {
+      const char* base = vt + v_off[dblk];
+      VOperand t;
+      t.s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
+      t.s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
+      v0[dblk] = t.v;
+    }
+  };
+
   f32x16 s_cur[2], s_nxt[2];
   // A wavefront whose 32 query rows all lie past t_k (ragged last query tile) keeps loading its share of
   // every tile and keeps the barriers, but leaves the matrix cores to the other workgroup on the unit.
@@ -332,13 +464,22 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
       if (cv) tile::convert_raw8<true>(raw_v, lds[decltype(vb0)::value][1], tid);
       if (ck || cv) __syncthreads();
     }
-    if (j + 2 < steps_all && has_tile(j + 2)) issue_k(j + 2, decltype(vb0)::value);  // K stage j & 1: read by step j-1
-    // V stage (j+1) & 1 likewise; the single-stream prologue has already fetched V(1)
-    if ((KS == 2 || j > 0) && has_tile(j + 1)) issue_v(j + 1, decltype(kb1)::value);
+    if constexpr (KS == 2) {  // two streams: the compiler's own order (a stream's last step may lack a successor tile)
+      if (j + 2 < steps_all && has_tile(j + 2)) issue_k(j + 2, decltype(vb0)::value);
+      if (has_tile(j + 1)) issue_v(j + 1, decltype(kb1)::value);
+      if (!active) return;
+      if (has_tile(j + 1)) scores(s_out, kb1);
+      accumulate(s_in, vb0);
+      if (has_tile(j + 1)) settle(j + 1, s_out);
+      return;
+    }
+    bf16x8 k0[NK / 4][2], v0[NV];
+    if (active) preload(k0, v0, kb1, vb0);
+    if (j + 2 < steps_all) issue_k(j + 2, decltype(vb0)::value);  // K stage j & 1: read by step j-1
+    if (j > 0) issue_v(j + 1, decltype(kb1)::value);  // V stage (j+1) & 1 likewise; the prologue has already fetched V(1)
     if (!active) return;
-    if (has_tile(j + 1)) scores(s_out, kb1);
-    accumulate(s_in, vb0);
-    if (has_tile(j + 1)) settle(j + 1, s_out);
+    const float mx = step_math(s_in, s_out, k0, v0, kb1, vb0);
+    raise(mask_tail(j + 1, s_out) ? lane_max(s_out) : mx);
   };
 
   // Prologue: all four tile stages are free, so K(0), V(0), K(1) and V(1) all go out at once: one memory round
