@@ -86,11 +86,23 @@ extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 //
 // D: head dimension, 128 or 64 (rows of 256 or 128 bytes, tiles of 16 or 8 KB, 8 or 4 MFMA steps per score block and
 // 4 or 2 accumulator blocks; the single-stream, bf16-cache instance only).
-template <int KS, bool FP8, int D>
-__global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(AttendParams p) {
+//
+// QS = 2, for launches that keep every compute unit busy for rounds of long walks: 8 wavefronts, one workgroup
+// per unit, 256 queries per workgroup; wavefronts 4-7 take the next 128 queries against the SAME key tiles, which
+// all eight wavefronts copy together (two instead of four copies per wavefront and tile).  A K/V tile then enters
+// the LDS once per 256 queries instead of once per 128: the copies, which cost the single-set instance 14-18 % of
+// its time at these scales whether they come from HBM or from L2, are halved per FLOP.  The two wavefronts of a SIMD
+// now pass the same barriers and so run the same part of the step at the same time; that costs nothing because
+// every slot of the hand-ordered step below mixes matrix and vector work (with the compiler's own order, score
+// MFMAs clustered apart from the exponentials, the same instance gained 1 % instead of 4-6 %).
+template <int KS, bool FP8, int D, int QS = 1>
+__global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void attend_bf16_kernel(AttendParams p) {
   static_assert(KS == 1 || KS == 2, "one or two key streams");
+  static_assert(QS == 1 || QS == 2, "one or two query sets");
   static_assert(!(FP8 && KS == 2), "the 8-bit cache path has one key stream");
   static_assert(D == 128 || (D == 64 && KS == 1 && !FP8), "d = 64: single stream, bf16 cache rows");
+  static_assert(QS == 1 || (KS == 1 && !FP8 && D == 128), "two query sets: single stream, bf16 cache rows, d = 128");
+  constexpr int NW = 4 * QS;  // wavefronts that share the copying of a tile
   constexpr int ROW_BYTES = 2 * D;            // one bf16 row
   constexpr int TILE_BYTES = BN * ROW_BYTES;  // 16 KB (d = 128) or 8 KB (d = 64)
   constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per row
@@ -105,13 +117,15 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
 
   if (static_cast<int>(blockIdx.x) >= p.attend_blocks) {  // fused append: a plain row copy by 256 lanes
     const int j = blockIdx.x - p.attend_blocks;
-    if (KS == 1 || threadIdx.x < 256) copy_rows_block(p.copy, j % p.ndesc, j / p.ndesc);
+    if ((KS == 1 && QS == 1) || threadIdx.x < 256) copy_rows_block(p.copy, j % p.ndesc, j / p.ndesc);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform, kept in a scalar register
   const int g = KS == 1 ? 0 : wave_all >> 2;                      // key stream of this wavefront
-  const int wave = wave_all & 3;                                  // its place among the four of the stream
+  const int qs = QS == 1 ? 0 : wave_all >> 2;                     // query set of this wavefront
+  const int wave = wave_all & 3;                                  // its place among the four of the stream / set
+  const int lw = QS == 1 ? wave : wave_all;                       // its place among the NW that copy a tile
   const int n = lane & 31, hl = lane >> 5;
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  All query tiles of one
@@ -146,7 +160,8 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
   const char* v_cur = reinterpret_cast<const char*>(static_cast<const bf16_t*>(p.v_cur) + cur_off);
 
   // Q as B operand: lane (n, hl) holds Q[row][16*ks + 8*hl .. +7] for ks = 0..7.
-  const int q_row = qt * BM + wave * 32 + n;
+  const int q_row0 = qt * (BM * QS) + qs * BM + wave * 32;  // first query row of this wavefront
+  const int q_row = q_row0 + n;
   bf16x8 qreg[NK];
   {
     const int ld = q_row < t_k ? q_row : t_k - 1;
@@ -167,8 +182,8 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
   // instructions (tile::issue_full / issue_ragged): the compiler then does not see an LDS store it would have to
   // order against the tile reads of the other buffer (it would wait for the whole prefetch in the middle of the
   // math).  Ordering is explicit instead: s_waitcnt vmcnt(0) and the workgroup barrier at the top of every step.
-  const int ld_off_k = tile::loader_off_k<ROW_BYTES>(wave, lane);
-  const int ld_off_v = tile::loader_off_v<ROW_BYTES>(wave, lane);
+  const int ld_off_k = tile::loader_off_k<ROW_BYTES>(lw, lane);
+  const int ld_off_v = tile::loader_off_v<ROW_BYTES>(lw, lane);
   const unsigned lds_base = static_cast<unsigned>(reinterpret_cast<unsigned long long>(
       (__attribute__((address_space(3))) char*)(&lds[0][0][0]))) + g * (4 * TILE_BYTES);
   int k_off[NK], v_off[NV];
@@ -207,9 +222,9 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
     const unsigned kd = lds_base + buf * (2 * TILE_BYTES);
     // Two separate statements under a workgroup-uniform branch: the full-tile path has no per-lane arithmetic.
     if (left >= BN)
-      tile::issue_full<ROW_BYTES>(kd, wave, ld_off_k, kb);
+      tile::issue_full<ROW_BYTES, NW>(kd, lw, ld_off_k, kb);
     else
-      tile::issue_ragged<false, ROW_BYTES>(kd, wave, lane, left, kb);
+      tile::issue_ragged<false, ROW_BYTES, NW>(kd, lw, lane, left, kb);
   };
   auto issue_v = [&](int j, int buf) {
     const int it = KS * j + g;
@@ -224,9 +239,9 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
     const unsigned vd = lds_base + buf * (2 * TILE_BYTES) + TILE_BYTES;
     if (left >= BN)
-      tile::issue_full<ROW_BYTES>(vd, wave, ld_off_v, vb);
+      tile::issue_full<ROW_BYTES, NW>(vd, lw, ld_off_v, vb);
     else
-      tile::issue_ragged<true, ROW_BYTES>(vd, wave, lane, left, vb);
+      tile::issue_ragged<true, ROW_BYTES, NW>(vd, lw, lane, left, vb);
   };
 
   // S^T = K Q^T for the 64 keys of the K tile in buffer `buf` x this wavefront's 32 queries.
@@ -448,7 +463,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
   f32x16 s_cur[2], s_nxt[2];
   // A wavefront whose 32 query rows all lie past t_k (ragged last query tile) keeps loading its share of
   // every tile and keeps the barriers, but leaves the matrix cores to the other workgroup on the unit.
-  const bool active = qt * BM + wave * 32 < t_k;
+  const bool active = q_row0 < t_k;
   // Steady-state step j (j + 1 < steps_all): K of the stream's tile j+1 sits in K stage kb1, V of its tile j in
   // V stage vb0.  s_in holds the scores of tile j, s_out receives those of tile j+1: the two register sets swap
   // roles from step to step instead of being copied.
@@ -487,7 +502,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
   // Loads return in issue order, so waiting until only the copies younger than K(0) are outstanding means that
   // K(0) has landed (CPT copies per wavefront and bf16 tile, two per 8-bit tile); tile 0 is a current-scale tile,
   // whose address does not depend on the head's run.
-  constexpr int CPT = TILE_BYTES / 4096;
+  constexpr int CPT = TILE_BYTES / (1024 * NW);
   if (KS == 1) {
     issue_k(0, 0);
     issue_v(0, 0);
@@ -537,12 +552,16 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
       __syncthreads();
     }
   }
-  if (KS == 1 && !active) return;
+  if (KS == 1 && QS == 1 && !active) return;
   if (active && has_tile(it)) {
     if (it & 1)
       accumulate(s_nxt, std::integral_constant<int, 1>{});
     else
       accumulate(s_cur, std::integral_constant<int, 0>{});
+  }
+  if constexpr (QS == 2) {  // the eight output tiles are staged over all four tile buffers: the V tiles must be done with
+    __syncthreads();
+    if (!active) return;
   }
   if constexpr (KS == 2) {
     // Stream 1 parks its accumulators (64 registers, one 256-byte row of LDS per register), row-sum partials and
@@ -576,7 +595,8 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
   // would be 8-byte pieces scattered over 32 rows.  The K buffers are idle by now (their last reader passed the
   // barrier above and no copy is in flight), so every wavefront stages its 32 x d tile in half a K stage, with the
   // 16-byte chunks XORed with the row number, and writes it out as whole rows, 1 KB per instruction.
-  char* stage = lds[wave >> 1][0] + (wave & 1) * (32 * ROW_BYTES);
+  char* stage = QS == 1 ? lds[wave >> 1][0] + (wave & 1) * (32 * ROW_BYTES)
+                        : reinterpret_cast<char*>(lds) + wave_all * (32 * ROW_BYTES);
 #pragma unroll
   for (int dblk = 0; dblk < NV; ++dblk)
 #pragma unroll
@@ -586,7 +606,7 @@ __global__ __launch_bounds__(256 * KS, KS == 1 ? 2 : 1) void attend_bf16_kernel(
       for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
       *reinterpret_cast<bf16x4*>(stage + n * ROW_BYTES + (((4 * dblk + g) ^ (n & (CPR - 1))) << 4) + 8 * hl) = v;
     }
-  const int out_row0 = qt * BM + wave * 32;
+  const int out_row0 = q_row0;
   bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(out_row0) * D;
   constexpr int ROWS_PER_STORE = 64 / CPR;  // CPR lanes write one row
 #pragma unroll
@@ -714,6 +734,11 @@ constexpr int TWO_STREAM_LDS_BYTES = 2 * 2 * 2 * TILE_BYTES_D128;  // two stream
 constexpr int FP8_LDS_BYTES = 2 * 2 * TILE_BYTES_D128 + 2 * tile::RAW8_BYTES;  // two stages x (K, V) + two landing buffers
 constexpr int TWO_STREAM_MAX_BLOCKS = 256;                    // compute units of the chip
 constexpr int TWO_STREAM_MIN_TOKENS = 384;                    // shorter walks gain nothing (measured at 256)
+// Two query sets per workgroup: from this scale size on, when the launch still gives every compute unit two rounds
+// of such workgroups (measured: a single round of 256 is slower than 512 workgroups of 128 queries), and when the
+// last 256-query tile is not mostly empty (1600 tokens: 7 tiles, the last one a quarter full, measured slower).
+constexpr int TWO_SET_MIN_TOKENS = 1024;
+constexpr int TWO_SET_MIN_BLOCKS = 512;
 
 // 128 KB of dynamic LDS need the function attribute raised, once per device.
 hipError_t allow_two_stream_lds() {
@@ -785,6 +810,14 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
       const hipError_t e = allow_two_stream_lds();
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL((attend_bf16_kernel<2, false, 128>), grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
+    } else if (const int wide = (a.t_k + 2 * BM - 1) / (2 * BM);
+               a.t_k >= TWO_SET_MIN_TOKENS && unsigned(wide) * pairs8 >= unsigned(TWO_SET_MIN_BLOCKS) &&
+               (wide * 2 * BM - a.t_k) * 16 <= a.t_k) {
+      // Long walks on a full chip: 256 queries per workgroup share every K/V tile.
+      p.n_qtiles = wide;
+      p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
+      hipLaunchKernelGGL((attend_bf16_kernel<1, false, 128, 2>), dim3(unsigned(p.attend_blocks) + copy_blocks),
+                         dim3(512), 0, stream, p);
     } else {
       hipLaunchKernelGGL((attend_bf16_kernel<1, false, 128>), grid, dim3(256), 0, stream, p);
     }

@@ -89,23 +89,25 @@ __device__ __forceinline__ void copy_1k_ragged(unsigned lds_dst, int lane_off, c
 }
 
 // This wavefront's copies of a full tile: `src` = first byte of the tile's 64 contiguous rows, `lds_tile` =
-// LDS byte address of the tile, lane_off = loader_off_k / loader_off_v.
-template <int RB = ROW_BYTES>
+// LDS byte address of the tile, lane_off = loader_off_k / loader_off_v.  NW wavefronts (`wave` = 0..NW-1) share a
+// tile: each copies ROWS * RB / (1024 NW) KB of it, instruction j covering the KB at (NW j + wave).
+template <int RB = ROW_BYTES, int NW = 4>
 __device__ __forceinline__ void issue_full(unsigned lds_tile, int wave, int lane_off, const char* src) {
 #pragma unroll
-  for (int j = 0; j < ROWS * RB / 4096; ++j) copy_1k(lds_tile + wave * 1024 + j * 4096, lane_off, src + j * 4096);
+  for (int j = 0; j < ROWS * RB / (1024 * NW); ++j)
+    copy_1k(lds_tile + wave * 1024 + j * (1024 * NW), lane_off, src + j * (1024 * NW));
 }
 // The same for a tile with only `left` (1..63) valid rows: rows past the end re-read the last valid row (the
 // caller masks their scores).  SWZ_V selects the V swizzle.
-template <bool SWZ_V, int RB = ROW_BYTES>
+template <bool SWZ_V, int RB = ROW_BYTES, int NW = 4>
 __device__ __forceinline__ void issue_ragged(unsigned lds_tile, int wave, int lane, int left, const char* src) {
   const int row0 = loader_row0<RB>(wave, lane);
 #pragma unroll
-  for (int j = 0; j < ROWS * RB / 4096; ++j) {
-    const int row = row0 + (4096 / RB) * j;
+  for (int j = 0; j < ROWS * RB / (1024 * NW); ++j) {
+    const int row = row0 + (1024 * NW / RB) * j;
     const int rr = row < left ? row : left - 1;
     const int off = rr * RB + (((lane & (RB / 16 - 1)) ^ (SWZ_V ? swizzle_v<RB>(row) : swizzle_k<RB>(row))) << 4);
-    copy_1k_ragged(lds_tile + wave * 1024 + j * 4096, off, src);
+    copy_1k_ragged(lds_tile + wave * 1024 + j * (1024 * NW), off, src);
   }
 }
 

@@ -235,6 +235,18 @@ def test_bf16_two_key_streams_per_workgroup():
     _bf16_case(2, 3, (1, 3, 20, 22), 1, 2, 1, seed=22)
 
 
+def test_bf16_two_query_sets_per_workgroup():
+    # Scales of 1024 tokens and more whose launch gives every compute unit at least two rounds of them use the
+    # instance whose workgroups take 256 queries (eight wavefronts sharing every K/V tile), unless the last such
+    # tile would be mostly empty.
+    # 1225 tokens on 104 (batch row, head) pairs: the last query tile holds 201 rows (second set: two full
+    # wavefronts, one with 9 rows, one idle); ragged key tiles; fused = separate bit for bit.
+    _bf16_case(1, 13, (1, 2, 4, 8, 35), 2, 3, 8, seed=91, sample_from=4, fused=True)
+    # 4150 tokens (a 50 x 83 map) on 32 pairs, every prior scale retained: 17 query tiles, the last with 54 rows
+    # (first set: one full wavefront and one with 22 rows; the second set idle but still copying its share).
+    _bf16_case(1, 4, ((1, 1), (2, 2), (4, 4), (35, 35), (50, 83)), 1, 1, 8, seed=92, sample_from=3)
+
+
 def test_bf16_head_dimension_64():
     # rows of 128 bytes: 8 KB tiles, four MFMA steps per score block, two accumulator blocks, its own swizzles.
     # Ragged tails in both directions, several tiles per head, fused = separate, and 1024-token scales.
