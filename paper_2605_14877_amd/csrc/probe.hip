@@ -53,8 +53,8 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint4* ops, float
 // Tile-step model: the instruction mix, dependencies and memory traffic of one step of the bf16 attention
 // kernel (per wavefront and 64-key tile: 16 score MFMAs fed from an LDS K tile, 32 scale FMAs, 32 exp2, 16
 // packs, 16 pair sums, 16 PV MFMAs fed from an LDS V tile through transposing reads, a 32-value max chain,
-// one barrier, and the HBM/L2 -> LDS copies of the next K and V tiles), without any of the kernel's
-// bookkeeping: no ragged tiles, no masks, no rescaling, every workgroup streams the same 2 MB of tiles (they
+// one barrier, and the HBM/L2 -> LDS copies of the next K and V tiles, in the kernel's hand-fixed issue order),
+// without any of the kernel's bookkeeping: no ragged tiles, no masks, no rescaling, every workgroup streams the same 2 MB of tiles (they
 // stay in L2).  Its throughput is what this mix sustains on the chip at hand; the numbers it computes mean
 // nothing.  Two workgroups of four wavefronts per compute unit, as in the kernel.
 // ---------------------------------------------------------------------------
@@ -116,56 +116,94 @@ __global__ __launch_bounds__(256, 2) void probe_tile_step_kernel(const char* kv,
     } s;
     bf16x8 v;
   };
-  auto step = [&](int it, auto buf_tag) {
+  // One step in the attention kernel's hand-fixed issue order: 32 slots, one MFMA each followed by its share of
+  // the vector and LDS work, scheduling fences between them.  Phases S(g) (the two K-steps of the score product that
+  // go with 16-key chunk g, both 32-key blocks) and A(g) (P V of chunk g) alternate; the probabilities of chunk 0
+  // are computed in the slots of S(0), those of chunk g+1 in the slots of A(g) and S(g+1), the maxima of the new
+  // scores in the slots of A(3); every LDS operand is read a phase before its MFMA, the first ones right after
+  // the barrier.
+  auto step = [&](int it, auto buf_tag, f32x16 (&s_in)[2], f32x16 (&s_out)[2]) {
     constexpr int buf = decltype(buf_tag)::value;
     wait_vmcnt<0>();
     __syncthreads();
-    issue(it + 2, buf, 0);
-    issue(it + 1, buf ^ 1, 1);
     const char* kt = lds[buf ^ 1][0];
     const char* vt = lds[buf][1];
+    bf16x8 kop[8][2], vop[4][4];
+    float e[4][8];
+    PB pb[4];
+    auto load_k = [&](int ks, int cb) {
+      kop[ks][cb] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * kRowBytes + k_off[ks]);
+    };
+    auto load_v = [&](int chunk, int d) {
+      const char* base = vt + 16 * chunk * kRowBytes + v_off[d];
+      VOperand t;
+      t.s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
+      t.s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * kRowBytes));
+      vop[chunk][d] = t.v;
+    };
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) load_k(i, cb);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) load_v(0, d);
+    issue(it + 2, buf, 0);
+    issue(it + 1, buf ^ 1, 1);
     const float mc = m_run * c;
+    auto p_half = [&](int chunk, int u) {
+      const int cb = chunk >> 1, r = 8 * (chunk & 1) + u;
+      e[chunk][u] = fast_exp2(fmaf(s_in[cb][r], c, -mc));
+      if (u & 1) {
+        pb[chunk].h[u >> 1] = bf16x2{static_cast<bf16_t>(e[chunk][u - 1]), static_cast<bf16_t>(e[chunk][u])};
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pb[chunk].h[u >> 1], ones, l_run, false);
+      }
+    };
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s_nxt[cb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) s_out[cb][r] = 0.f;
+    fence();
+    float mx = -INFINITY;
+    auto s_slot = [&](int gch, int i, int& half) {
+      const int ks = 2 * gch + (i >> 1), cb = i & 1;
+      s_out[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks][cb], qreg[ks], s_out[cb], 0, 0, 0);
+      fence();
+      if (gch < 3) load_k(ks + 2, cb);
+      const int n = gch == 0 ? 2 : 1;
+      for (int u = 0; u < n; ++u) p_half(gch, half++);
+      fence();
+    };
+    int half = 0;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int i = 0; i < 4; ++i) s_slot(0, i, half);
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * kRowBytes + k_off[ks]);
-        s_nxt[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s_nxt[cb], 0, 0, 0);
-      }
-#pragma unroll
-    for (int chunk = 0; chunk < 4; ++chunk) {
-      const int cb = chunk >> 1, ks = chunk & 1;
-      VOperand va[4];
+    for (int gch = 0; gch < 4; ++gch) {
+      half = 0;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        const char* base = vt + 16 * chunk * kRowBytes + v_off[d];
-        va[d].s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
-        va[d].s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * kRowBytes));
+        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[gch][d], pb[gch].v, o[d], 0, 0, 0);
+        fence();
+        if (gch < 3) {
+          load_v(gch + 1, d);
+          p_half(gch + 1, half++);
+        } else {
+#pragma unroll
+          for (int r = 8 * d; r < 8 * d + 8; ++r) mx = fmaxf(mx, s_out[r >> 4][r & 15]);
+          asm volatile("" : "+v"(mx));
+        }
+        fence();
       }
-      PB pb;
+      if (gch < 3) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) pb.v[j] = static_cast<bf16_t>(fast_exp2(fmaf(s_cur[cb][8 * ks + j], c, -mc)));
-#pragma unroll
-      for (int j = 0; j < 4; ++j) l_run = __builtin_amdgcn_fdot2_f32_bf16(pb.h[j], ones, l_run, false);
-#pragma unroll
-      for (int d = 0; d < 4; ++d) o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[d].v, pb.v, o[d], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) s_slot(gch + 1, i, half);
+      }
     }
-    float mx = s_nxt[0][0];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_nxt[cb][r]);
-    m_run = fmaxf(m_run, mx * 1e-6f);
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) s_cur[cb] = s_nxt[cb];
+    m_run = fmaxf(m_run, max_halves(mx) * 1e-6f);
   };
-  for (int it = 0; it < iters; it += 2) {
-    step(it, std::integral_constant<int, 0>{});
-    step(it + 1, std::integral_constant<int, 1>{});
+  for (int it = 0; it < iters; it += 2) {  // the two score sets swap roles from step to step
+    step(it, std::integral_constant<int, 0>{}, s_cur, s_nxt);
+    step(it + 1, std::integral_constant<int, 1>{}, s_nxt, s_cur);
   }
   wait_vmcnt<0>();
   float acc = l_run + m_run;
