@@ -354,15 +354,16 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
   //   A(g): P V for the 16 keys of chunk g (NV MFMAs)
   //   order S(0) A(0) S(1) A(1) S(2) A(2) S(3) A(3).  P(0) is computed in the slots of S(0), P(g+1) in those of
   //   A(g) and S(g+1), the row maxima of the new scores in those of A(3); the K operands of S(g+1) are read in the
-  //   slots of S(g), the V operands of A(g+1) in those of A(g): every operand a whole phase before its MFMA.
+  //   slots of S(g), the V operands of A(g+1) in those of A(g): every operand a whole phase before its MFMA (those
+  //   of S(0) and A(0), which only exist after the barrier, in preload() and in the slots of S(0)).
   // Returns this lane's maximum over the new scores (before any tail mask).
-  auto step_math = [&](const f32x16 (&s_in)[2], f32x16 (&s_out)[2], const bf16x8 (&k0)[NK / 4][2],
-                       const bf16x8 (&v0)[NV], auto kb1, auto vb0) {
+  auto step_math = [&](const f32x16 (&s_in)[2], f32x16 (&s_out)[2], const bf16x8 (&k0)[2], auto kb1, auto vb0) {
     constexpr int KPC = NK / 4;          // K-steps per phase S
     constexpr int NS = 2 * KPC;          // slots of a phase S
     constexpr int NA = NV;               // slots of a phase A
     constexpr int HALVES = 8;            // a chunk's probabilities come in 8 half units (one probability per lane each)
     static_assert(HALVES % NS == 0 && HALVES % (NS + NA) == 0, "phases divide the vector work evenly");
+    static_assert(NS == NA, "one V block of A(0) is read per slot of S(0)");
     const char* kt = lds[2 * g + decltype(kb1)::value][0];
     const char* vt = lds[2 * g + decltype(vb0)::value][1];
     const float mc = m_run * c;
@@ -398,16 +399,16 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_out[cb][r] = 0.f;
 #pragma unroll
-    for (int i = 0; i < KPC; ++i)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) kop[i][cb] = k0[i][cb];
-#pragma unroll
-    for (int dblk = 0; dblk < NV; ++dblk) vop[0][dblk] = v0[dblk];
+    for (int cb = 0; cb < 2; ++cb) kop[0][cb] = k0[cb];
     float mx = -INFINITY;
     auto s_slot = [&](int gch, int i, int halves_chunk, int& half) {  // slot i of phase S(gch)
       const int ks = gch * KPC + (i >> 1), cb = i & 1;
       s_out[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks][cb], qreg[ks], s_out[cb], 0, 0, 0);
       fence();
+      if (gch == 0) {  // the rest of this phase's K operands, and the V operands of A(0)
+        if (ks + 1 < KPC) load_k(ks + 1, cb);
+        load_v(0, i);
+      }
       if (gch < 3) load_k(ks + KPC, cb);
       const int n = gch == 0 ? HALVES / NS : HALVES / (NS + NA);
       for (int u = 0; u < n; ++u) p_half(halves_chunk, half++);
@@ -441,23 +442,14 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
     }
     return mx;
   };
-  // The first operands of a step (K-steps of phase S(0), V blocks of phase A(0)): read right after the barrier,
-  // before the step's tile copies are issued, so that their LDS round trip passes under the scalar work of issuing.
-  auto preload = [&](bf16x8 (&k0)[NK / 4][2], bf16x8 (&v0)[NV], auto kb1, auto vb0) {
+  // The K operands of a step's first two MFMAs: read right after the barrier, before the step's tile copies are
+  // issued, so that their LDS round trip passes under the scalar work of issuing.  Only those: right after a
+  // barrier all wavefronts of the workgroup read at once, and what they ask for queues up in front of the first
+  // MFMA; everything else is read from the slots of phase S(0) on.
+  auto preload = [&](bf16x8 (&k0)[2], auto kb1) {
     const char* kt = lds[2 * g + decltype(kb1)::value][0];
-    const char* vt = lds[2 * g + decltype(vb0)::value][1];
 #pragma unroll
-    for (int i = 0; i < NK / 4; ++i)
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) k0[i][cb] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[i]);
-#pragma unroll
-    for (int dblk = 0; dblk < NV; ++dblk) {
-      const char* base = vt + v_off[dblk];
-      VOperand t;
-      t.s.lo = lds_read_tr16(reinterpret_cast<const bf16_t*>(base));
-      t.s.hi = lds_read_tr16(reinterpret_cast<const bf16_t*>(base + 8 * ROW_BYTES));
-      v0[dblk] = t.v;
-    }
+    for (int cb = 0; cb < 2; ++cb) k0[cb] = *reinterpret_cast<const bf16x8*>(kt + cb * 32 * ROW_BYTES + k_off[0]);
   };
 
   f32x16 s_cur[2], s_nxt[2];
@@ -488,12 +480,12 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
       if (has_tile(j + 1)) settle(j + 1, s_out);
       return;
     }
-    bf16x8 k0[NK / 4][2], v0[NV];
-    if (active) preload(k0, v0, kb1, vb0);
+    bf16x8 k0[2];
+    if (active) preload(k0, kb1);
     if (j + 2 < steps_all) issue_k(j + 2, decltype(vb0)::value);  // K stage j & 1: read by step j-1
     if (j > 0) issue_v(j + 1, decltype(kb1)::value);  // V stage (j+1) & 1 likewise; the prologue has already fetched V(1)
     if (!active) return;
-    const float mx = step_math(s_in, s_out, k0, v0, kb1, vb0);
+    const float mx = step_math(s_in, s_out, k0, kb1, vb0);
     raise(mask_tail(j + 1, s_out) ? lane_max(s_out) : mx);
   };
 
@@ -597,6 +589,11 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
   // 16-byte chunks XORed with the row number, and writes it out as whole rows, 1 KB per instruction.
   char* stage = QS == 1 ? lds[wave >> 1][0] + (wave & 1) * (32 * ROW_BYTES)
                         : reinterpret_cast<char*>(lds) + wave_all * (32 * ROW_BYTES);
+  // The lane numbers used from here on are formed anew from the work-item id, hidden from the optimiser, so that
+  // they are not kept in registers (or spilled) across the tile loop, which has none to spare.
+  int tid_o = threadIdx.x;
+  asm volatile("" : "+v"(tid_o));
+  const int lane_o = tid_o & 63, n_o = lane_o & 31, hl_o = lane_o >> 5;
 #pragma unroll
   for (int dblk = 0; dblk < NV; ++dblk)
 #pragma unroll
@@ -604,14 +601,14 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
       bf16x4 v;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = static_cast<bf16_t>(o[dblk][4 * g + e] * inv);
-      *reinterpret_cast<bf16x4*>(stage + n * ROW_BYTES + (((4 * dblk + g) ^ (n & (CPR - 1))) << 4) + 8 * hl) = v;
+      *reinterpret_cast<bf16x4*>(stage + n_o * ROW_BYTES + (((4 * dblk + g) ^ (n_o & (CPR - 1))) << 4) + 8 * hl_o) = v;
     }
   const int out_row0 = q_row0;
   bf16_t* op = static_cast<bf16_t*>(p.out) + cur_off + static_cast<long long>(out_row0) * D;
   constexpr int ROWS_PER_STORE = 64 / CPR;  // CPR lanes write one row
 #pragma unroll
   for (int r = 0; r < 32 / ROWS_PER_STORE; ++r) {
-    const int row = ROWS_PER_STORE * r + lane / CPR, slot = lane & (CPR - 1);
+    const int row = ROWS_PER_STORE * r + lane_o / CPR, slot = lane_o & (CPR - 1);
     const uint4 v = *reinterpret_cast<const uint4*>(stage + row * ROW_BYTES + ((slot ^ (row & (CPR - 1))) << 4));
     if (out_row0 + row < t_k) *reinterpret_cast<uint4*>(op + row * D + slot * 8) = v;
   }
