@@ -78,7 +78,7 @@ extern __shared__ __attribute__((aligned(1024))) char attend_dynamic_lds[];
 // output, row sums and references to stream 0 through LDS.  The unit then runs two wavefronts per SIMD, as it
 // does when two workgroups share it, without a second pass over HBM.
 //
-// FP8: the arenas hold FP8 E4M3 codes, 128 bytes per row (single-stream instance only).  A tile of the retained run
+// FP8: the arenas hold FP8 E4M3 codes, 128 bytes per row (single-stream instances only).  A tile of the retained run
 // lands as it is (8 KB) in a landing buffer behind the tile stages, one for K and one for V, and at the top of the
 // step that first needs it the whole workgroup rewrites it as a bf16 tile in its stage (exact: every E4M3 value is
 // a bf16 value), with one more barrier; from there on the step is the same.  Current-scale tiles are bf16 and go
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
   static_assert(QS == 1 || QS == 2, "one or two query sets");
   static_assert(!(FP8 && KS == 2), "the 8-bit cache path has one key stream");
   static_assert(D == 128 || (D == 64 && KS == 1 && !FP8), "d = 64: single stream, bf16 cache rows");
-  static_assert(QS == 1 || (KS == 1 && !FP8 && D == 128), "two query sets: single stream, bf16 cache rows, d = 128");
+  static_assert(QS == 1 || (KS == 1 && D == 128), "two query sets: single stream, d = 128");
   constexpr int NW = 4 * QS;  // wavefronts that share the copying of a tile
   constexpr int ROW_BYTES = 2 * D;            // one bf16 row
   constexpr int TILE_BYTES = BN * ROW_BYTES;  // 16 KB (d = 128) or 8 KB (d = 64)
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
     if (FP8 && prior) {  // codes land in the K landing buffer; the step that needs the tile converts it
-      tile::issue_raw8(lds_base + 4 * TILE_BYTES, wave, lane, left, k_prior + static_cast<long long>(local) * PRIOR_TILE_BYTES);
+      tile::issue_raw8<NW>(lds_base + 4 * TILE_BYTES, lw, lane, left, k_prior + static_cast<long long>(local) * PRIOR_TILE_BYTES);
       return;
     }
     const char* kb = (prior ? k_prior : k_cur) + static_cast<long long>(local) * TILE_BYTES;
@@ -232,8 +232,8 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
     const int local = prior ? it - tiles_cur : it;
     const int left = (prior ? n_prior : t_k) - local * BN;
     if (FP8 && prior) {
-      tile::issue_raw8(lds_base + 4 * TILE_BYTES + tile::RAW8_BYTES, wave, lane, left,
-                       v_prior + static_cast<long long>(local) * PRIOR_TILE_BYTES);
+      tile::issue_raw8<NW>(lds_base + 4 * TILE_BYTES + tile::RAW8_BYTES, lw, lane, left,
+                           v_prior + static_cast<long long>(local) * PRIOR_TILE_BYTES);
       return;
     }
     const char* vb = (prior ? v_prior : v_cur) + static_cast<long long>(local) * TILE_BYTES;
@@ -467,8 +467,8 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
       // V(j) likewise.  Their stages are free (last read in step j-2), the landing buffers are free again after
       // the barrier, before this step's copies go out.
       const bool ck = j + 1 < tiles_all && j + 1 >= tiles_cur, cv = j >= tiles_cur;
-      if (ck) tile::convert_raw8<false>(raw_k, lds[decltype(kb1)::value][0], tid);
-      if (cv) tile::convert_raw8<true>(raw_v, lds[decltype(vb0)::value][1], tid);
+      if (ck) tile::convert_raw8<false, 64 * NW>(raw_k, lds[decltype(kb1)::value][0], tid);
+      if (cv) tile::convert_raw8<true, 64 * NW>(raw_v, lds[decltype(vb0)::value][1], tid);
       if (ck || cv) __syncthreads();
     }
     if constexpr (KS == 2) {  // two streams: the compiler's own order (a stream's last step may lack a successor tile)
@@ -501,8 +501,8 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
     if (tiles_all > 1) {
       issue_k(1, 1);
       issue_v(1, 1);
-      if (FP8 && tiles_cur == 1)
-        wait_vmcnt<CPT + 4>();
+      if (FP8 && tiles_cur == 1)  // tile 1 arrives as codes: 8 / NW copies per wavefront for each of K(1), V(1)
+        wait_vmcnt<CPT + 2 * (8 / NW)>();
       else
         wait_vmcnt<3 * CPT>();
     } else {
@@ -538,9 +538,9 @@ __global__ __launch_bounds__(256 * KS * QS, (KS == 1 && QS == 1) ? 2 : 1) void a
   if constexpr (FP8) {
     if (it >= tiles_cur) {  // V of the last tile is still in its landing buffer
       if (it & 1)
-        tile::convert_raw8<true>(raw_v, lds[1][1], tid);
+        tile::convert_raw8<true, 64 * NW>(raw_v, lds[1][1], tid);
       else
-        tile::convert_raw8<true>(raw_v, lds[0][1], tid);
+        tile::convert_raw8<true, 64 * NW>(raw_v, lds[0][1], tid);
       __syncthreads();
     }
   }
@@ -749,6 +749,9 @@ hipError_t allow_two_stream_lds() {
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<1, true, 128>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FP8_LDS_BYTES);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<1, true, 128, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FP8_LDS_BYTES);
   if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
   return e;
 }
@@ -796,25 +799,33 @@ hipError_t launch_attend(const AttendArgs& a, hipStream_t stream) {
     const unsigned pairs8 = (unsigned(a.H) * a.batch + 7) / 8 * 8;  // padded so that id % 8 is the XCD
     p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
     const dim3 grid(unsigned(p.attend_blocks) + copy_blocks);
+    // Long walks on a full chip: 256 queries per workgroup share every K/V tile (d = 128, either cache format).
+    const int wide = (a.t_k + 2 * BM - 1) / (2 * BM);
+    const bool two_sets = a.d == 128 && a.t_k >= TWO_SET_MIN_TOKENS &&
+                          unsigned(wide) * pairs8 >= unsigned(TWO_SET_MIN_BLOCKS) && (wide * 2 * BM - a.t_k) * 16 <= a.t_k;
+    const unsigned wide_blocks = unsigned(wide) * pairs8;
     if (a.d == 64) {  // rows of 128 bytes: the single-stream instance
       hipLaunchKernelGGL((attend_bf16_kernel<1, false, 64>), grid, dim3(256), 0, stream, p);
-    } else if (a.kv_fp8) {  // 8-bit cache rows: the single-stream instance with landing buffers
+    } else if (a.kv_fp8) {  // 8-bit cache rows: the single-stream instances with landing buffers
       const hipError_t e = allow_two_stream_lds();
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((attend_bf16_kernel<1, true, 128>), grid, dim3(256), FP8_LDS_BYTES, stream, p);
+      if (two_sets) {
+        p.n_qtiles = wide;
+        p.attend_blocks = int(wide_blocks);
+        hipLaunchKernelGGL((attend_bf16_kernel<1, true, 128, 2>), dim3(wide_blocks + copy_blocks), dim3(512),
+                           FP8_LDS_BYTES, stream, p);
+      } else {
+        hipLaunchKernelGGL((attend_bf16_kernel<1, true, 128>), grid, dim3(256), FP8_LDS_BYTES, stream, p);
+      }
     } else if (p.attend_blocks <= TWO_STREAM_MAX_BLOCKS && a.t_k >= TWO_STREAM_MIN_TOKENS) {
       // At most one workgroup per compute unit: two key streams per workgroup put two wavefronts on every SIMD.
       const hipError_t e = allow_two_stream_lds();
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL((attend_bf16_kernel<2, false, 128>), grid, dim3(512), TWO_STREAM_LDS_BYTES, stream, p);
-    } else if (const int wide = (a.t_k + 2 * BM - 1) / (2 * BM);
-               a.t_k >= TWO_SET_MIN_TOKENS && unsigned(wide) * pairs8 >= unsigned(TWO_SET_MIN_BLOCKS) &&
-               (wide * 2 * BM - a.t_k) * 16 <= a.t_k) {
-      // Long walks on a full chip: 256 queries per workgroup share every K/V tile.
+    } else if (two_sets) {
       p.n_qtiles = wide;
-      p.attend_blocks = int(unsigned(p.n_qtiles) * pairs8);
-      hipLaunchKernelGGL((attend_bf16_kernel<1, false, 128, 2>), dim3(unsigned(p.attend_blocks) + copy_blocks),
-                         dim3(512), 0, stream, p);
+      p.attend_blocks = int(wide_blocks);
+      hipLaunchKernelGGL((attend_bf16_kernel<1, false, 128, 2>), dim3(wide_blocks + copy_blocks), dim3(512), 0, stream, p);
     } else {
       hipLaunchKernelGGL((attend_bf16_kernel<1, false, 128>), grid, dim3(256), 0, stream, p);
     }

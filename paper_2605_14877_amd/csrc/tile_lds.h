@@ -112,32 +112,36 @@ __device__ __forceinline__ void issue_ragged(unsigned lds_tile, int wave, int la
 }
 
 // 8-bit cache rows (FP8 E4M3 codes, 128 bytes per row): a 64-row tile is 8 KB and lands in LDS as it lies in
-// memory, 2 KB per wavefront in two copies; `left` < 64: rows past the end re-read the last valid row.
+// memory, 8 / NW KB per wavefront (NW wavefronts share a tile) in copies of 1 KB; `left` < 64: rows past the end
+// re-read the last valid row.
 constexpr int RAW8_ROW_BYTES = 128;
 constexpr int RAW8_BYTES = ROWS * RAW8_ROW_BYTES;
+template <int NW = 4>
 __device__ __forceinline__ void issue_raw8(unsigned lds_tile, int wave, int lane, int left, const char* src) {
+  constexpr int PER_WAVE = RAW8_BYTES / NW;  // bytes of the tile this wavefront copies
   if (left >= ROWS) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) copy_1k(lds_tile + wave * 2048 + j * 1024, lane * 16, src + wave * 2048 + j * 1024);
+    for (int j = 0; j < PER_WAVE / 1024; ++j)
+      copy_1k(lds_tile + wave * PER_WAVE + j * 1024, lane * 16, src + wave * PER_WAVE + j * 1024);
   } else {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int row = 16 * wave + 8 * j + (lane >> 3);
+    for (int j = 0; j < PER_WAVE / 1024; ++j) {
+      const int row = (ROWS / NW) * wave + 8 * j + (lane >> 3);
       const int rr = row < left ? row : left - 1;
-      copy_1k_ragged(lds_tile + wave * 2048 + j * 1024, rr * RAW8_ROW_BYTES + (lane & 7) * 16, src);
+      copy_1k_ragged(lds_tile + wave * PER_WAVE + j * 1024, rr * RAW8_ROW_BYTES + (lane & 7) * 16, src);
     }
   }
 }
-// Turns a landed 8-bit tile (`raw`, LDS) into the bf16 tile format at `stage` (LDS): 256 lanes, four groups of
+// Turns a landed 8-bit tile (`raw`, LDS) into the bf16 tile format at `stage` (LDS): NT lanes, 1024 / NT groups of
 // eight codes each; every E4M3 value is a bf16 value, so the conversion is exact.  SWZ_V selects the V swizzle.
-template <bool SWZ_V>
+template <bool SWZ_V, int NT = 256>
 __device__ __forceinline__ void convert_raw8(const char* raw, char* stage, int tid) {
   // The per-lane offsets below are cheap; made opaque here so that they are recomputed on the spot instead of being
   // kept in registers across the caller's tile loop, which has none to spare.
   asm volatile("" : "+v"(tid));
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int idx = tid + 256 * i;
+  for (int i = 0; i < 1024 / NT; ++i) {
+    const int idx = tid + NT * i;
     const int row = idx >> 4, lc = idx & 15;
     const uint2 w = *reinterpret_cast<const uint2*>(raw + row * RAW8_ROW_BYTES + lc * 8);
     union {

@@ -139,6 +139,20 @@ def test_attention_over_the_8_bit_cache_matches_the_oracle(L, H, sides, s, den, 
     print(f"fp8 cache {sides}: worst |err| {worst:.4f}")
 
 
+def test_8_bit_cache_with_two_query_sets_per_workgroup():
+    # 1225 tokens on 104 (batch row, head) pairs: the launch takes the instance whose workgroups hold 256 queries
+    # (eight wavefronts copy and convert every tile together); the last query tile has a partly filled second set,
+    # the retained runs end in ragged 8-bit tiles; one launch or two: the same bits.
+    t0, c, K, d, shape, plan, ref, qkv = _case(1, 13, (1, 2, 4, 8, 35), 2, 3, 8, seed=76)
+    sm = 1.0 / np.sqrt(d)
+    sep = _run(plan, qkv, t0, c, sm)
+    fused = _run(plan, qkv, t0, c, sm, fused_layers=(0,))
+    for a, b in zip(sep[0], fused[0]):
+        assert torch.equal(a, b)
+    worst = _check_attention(sep, qkv, t0, ref["present"], sm, sample_from=4)
+    print(f"fp8 cache, two query sets: worst |err| {worst:.4f}")
+
+
 def test_layer2b_full_size_with_8_bit_cache():
     # one 2B-like layer at its real shape; the same byte budget as the bf16 case now holds twice the tokens
     cfg = hi.CONFIGS["layer2b"]
