@@ -553,6 +553,32 @@ def stack_measure(name, dev, passes, warmup, generation=True, batched=True, fp8_
             })
         out.update({"attend_ms_per_pass_kernel_only": round(float(att_us.sum()) * L / 1e3, 3),
                     "append_ms_per_pass_kernel_only": round(float(app_us.sum()) * L / 1e3, 3), "per_scale": rows})
+        if kv_format == hk.KV_NATIVE:
+            # The same launches of the largest scale on all-zero Q, K, V and cache rows: the same instructions, the
+            # same memory traffic, but operand bits that do not make the chip lower its clock.  A diagnostic of
+            # what the kernel's instruction stream sustains when power is not the limit; not a result.
+            kk = K - 1
+            zq, zk, zv = (torch.zeros_like(x) for x in acts[0][kk][:3])
+            zo = torch.empty_like(zq)
+            ka.zero_()
+            va.zero_()
+            n_l = min(L, 8)
+            best = None
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for l in range(n_l):
+                    hk.heatkv_attend_scale(plan, l, kk, zq, zk, zv, ka, va, sm, zo)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / n_l
+                best = us if best is None else min(best, us)
+            fl = sum(4.0 * t0[kk] * d * nb * (int(plan.runs(kk, l)[1].astype(np.int64).sum()) + H * t0[kk])
+                     for l in range(n_l)) / n_l
+            out["largest_scale_on_zero_inputs"] = {
+                "t": t0[kk], "launches": n_l, "attend_us": round(best, 2), "tflops": round(fl / best / 1e6, 1),
+                "pct_mfma_peak": round(100 * fl / best / 1e6 / PEAK_BF16_TFLOPS, 2)}
+            del zq, zk, zv, zo
         return out
 
     result = measure(hk.KV_NATIVE)
@@ -590,7 +616,9 @@ def mfma_leg(stack):
     return {"kernel": "attend_bf16_kernel", "workload": stack["workload"], "bound": "mfma",
             "launches": [r["t"] for r in rows], "achieved": round(fl / us, 1), "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": round(fl / us / PEAK_BF16_TFLOPS, 4),
-            "per_scale": [{k: r[k] for k in ("t", "attend_us", "tflops", "pct_mfma_peak")} for r in rows]}
+            "per_scale": [{k: r[k] for k in ("t", "attend_us", "tflops", "pct_mfma_peak")} for r in rows],
+            # same kernel, same launches, all-zero operands (no clock throttling): diagnostic, see stack_measure
+            "largest_scale_on_zero_inputs": stack.get("largest_scale_on_zero_inputs")}
 
 
 def append_leg(stack):
