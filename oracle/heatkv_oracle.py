@@ -113,8 +113,8 @@ def attend_scale(q_seq, k_seq, v_seq, t, k, retained_scales, sm_scale):
 
 
 # --------------------------------------------------------------------------
-# 8-bit storage of the retained K/V (an extension of this build: the paper leaves quantisation of the cache to
-# future work, Sec. 5, and fixes no format; the format taken here is stated in the design doc)
+# 8-bit storage of the retained K/V (an extension: the paper leaves quantisation of the cache to future work,
+# Sec. 5, and fixes no format; the format taken here is the one described below)
 #
 # Stored rows are OCP FP8 E4M3 codes: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits; exponent field 0
 # holds subnormals m * 2^-9; exponent 15 with mantissa 7 is NaN; there are no infinities; the largest finite
